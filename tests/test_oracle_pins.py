@@ -1,0 +1,374 @@
+"""Pins for the CPU oracle: it is checked against what the paper and the
+mathematics fix, never against itself or the HIP path.
+
+  * hand-worked cases derived from the algorithm statements (tests/golden),
+  * an exact-integer brute force that compares Euclidean norms literally
+    (App. B.2 "Balancing without normalization") and builds the order from the
+    appended sign list with the list form of the reorder (Sec. 2.1 + the server
+    algorithm of Sec. 3.3) -- a different formulation from the oracle's
+    pointer form (App. C.1),
+  * invariants: greedy norm bound, running sum = signed sum of differences,
+    valid permutations, the prefix identities in the proof of Lemma 1,
+  * special cases: one worker, identical rows, power-of-two scaling.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from conftest import GOLDEN, load_hand_cases, load_reorder_cases
+
+HAND = load_hand_cases(os.path.join(GOLDEN, "hand_cases.txt"))
+
+
+# --------------------------------------------------------------------------- hand cases
+@pytest.mark.parametrize("case", HAND, ids=[c["name"] for c in HAND])
+def test_hand_cases(case):
+    out = oracle.server_epoch(case["rows"])
+    assert out["eps"].tolist() == case["eps"].tolist()
+    assert out["r"].tolist() == case["r"].tolist()
+    assert out["perm"].tolist() == case["perm"].tolist()
+
+
+def test_worker_order_matters():
+    """HB with the two workers swapped must give the other outcome (r=+1):
+    a walk that visited workers in another order would fail HB or this."""
+    hb = [c for c in HAND if c["name"] == "HB"][0]
+    swapped = hb["rows"][::-1].copy()
+    out = oracle.server_epoch(swapped)
+    assert out["r"].tolist() == [1.0]
+    assert out["eps"].tolist() == [[1], [-1]]      # worker (0,2) first: tie -> +1, then (0,1): -1
+
+
+# --------------------------------------------------------------------------- brute force
+def _brute_force_epoch(z_int, perm_in=None):
+    """Exact integer re-derivation.  z_int: nested python ints [m][n][d].
+
+    Decision by literal comparison of squared Euclidean norms; signs are appended
+    to one list per worker as (s, -s); the next order comes from the list form of
+    the reorder.  Returns (eps[m][n/2], r[d], perm[m][n]).
+    """
+    m, n, d = len(z_int), len(z_int[0]), len(z_int[0][0])
+    r = [0] * d
+    S = [[] for _ in range(m)]
+    eps = [[0] * (n // 2) for _ in range(m)]
+    for j in range(1, n + 1):
+        for i in range(m):
+            if j % 2:
+                continue
+            z1, z2 = z_int[i][j - 2], z_int[i][j - 1]
+            c = [a - b for a, b in zip(z1, z2)]
+            plus = sum((x + y) ** 2 for x, y in zip(r, c))
+            minus = sum((x - y) ** 2 for x, y in zip(r, c))
+            s = +1 if plus < minus else -1
+            r = [x + s * y for x, y in zip(r, c)]
+            S[i] += [s, -s]
+            eps[i][j // 2 - 1] = -s
+    perm = []
+    for i in range(m):
+        pos, neg = [], []
+        for j in range(n):
+            ident = j if perm_in is None else int(perm_in[i][j])
+            (pos if S[i][j] == +1 else neg).append(ident)
+        perm.append(pos + neg[::-1])
+    return eps, r, perm
+
+
+@pytest.mark.parametrize("seed,m,n,d,maxabs", [
+    (0, 1, 2, 1, 3), (1, 1, 8, 3, 2), (2, 3, 6, 4, 2), (3, 4, 10, 7, 5),
+    (4, 5, 4, 1, 1), (5, 2, 16, 2, 1), (6, 7, 12, 33, 9),
+])
+def test_brute_force_exact_integers(seed, m, n, d, maxabs):
+    z = workloads.integer_rows(seed, m, n, d, maxabs)
+    perm_in = workloads.random_perms(seed + 100, m, n)
+    want_eps, want_r, want_perm = _brute_force_epoch(z.astype(np.int64).tolist(), perm_in)
+    got = oracle.server_epoch(z, perm_in)
+    assert got["eps"].tolist() == want_eps
+    assert got["r"].tolist() == [float(v) for v in want_r]
+    assert got["perm"].tolist() == want_perm
+    # inputs with many exact ties must exist in this family, or the tie rule is untested
+    if maxabs <= 2 and m * n >= 16:
+        assert (got["t"] == 0).sum() >= 1
+
+
+def test_brute_force_rational_inputs():
+    """Dyadic-rational rows (exact in fp32) against exact Fraction arithmetic."""
+    rng = np.random.default_rng(11)
+    z = (rng.integers(-64, 65, size=(2, 8, 5)) / 16.0).astype(np.float32)
+    zi = [[[Fraction(float(v)) for v in row] for row in w] for w in z]
+    want_eps, want_r, want_perm = _brute_force_epoch(zi)
+    got = oracle.server_epoch(z)
+    assert got["eps"].tolist() == want_eps
+    assert got["r"].tolist() == [float(v) for v in want_r]
+    assert got["perm"].tolist() == want_perm
+
+
+# --------------------------------------------------------------------------- invariants
+def _flatten_pairs(z):
+    """rows[count][2][d] in the step-major, worker-minor order."""
+    m, n, d = z.shape
+    return np.ascontiguousarray(
+        z.reshape(m, n // 2, 2, d).transpose(1, 0, 2, 3).reshape(m * n // 2, 2, d))
+
+
+@pytest.mark.parametrize("maker", ["tiny", "heavy"])
+def test_greedy_bound_and_signed_sum(maker):
+    m, n, d = 4, 32, 96
+    z = workloads.tiny_epoch(5, m, n, d) if maker == "tiny" else workloads.heavy_rows(5, m, n, d)
+    out = oracle.server_epoch(z)
+    rows = _flatten_pairs(z).astype(np.float64)
+    diffs = rows[:, 1] - rows[:, 0]                      # z2 - z1 per flattened pair
+    eps_flat = out["eps"].T.reshape(-1).astype(np.float64)  # [k][i] order
+    # running sum = signed sum of the differences (closed form given the signs)
+    np.testing.assert_allclose(out["r"], (eps_flat[:, None] * diffs).sum(0), rtol=0, atol=1e-10)
+    # ||r_k||^2 <= sum_{j<=k} ||d_j||^2 at every step
+    prefix = np.cumsum(eps_flat[:, None] * diffs, axis=0)
+    lhs = (prefix ** 2).sum(1)
+    rhs = np.cumsum((diffs ** 2).sum(1))
+    assert np.all(lhs <= rhs * (1 + 1e-12))
+    # the decision really is the sign of the inner product seen at that time
+    before = np.vstack([np.zeros((1, d)), prefix[:-1]])
+    t = (before * diffs).sum(1)
+    np.testing.assert_allclose(out["t"].T.reshape(-1), t, rtol=1e-9, atol=1e-9)
+    assert np.all(np.where(t <= 0, 1, -1) == eps_flat)
+    # each step is no worse than the other sign would have been
+    other = ((before - eps_flat[:, None] * diffs) ** 2).sum(1)
+    assert np.all(lhs <= other * (1 + 1e-12))
+
+
+def test_permutations_valid_and_structured():
+    m, n, d = 5, 20, 17
+    z = workloads.tiny_epoch(8, m, n, d)
+    perm_in = workloads.random_perms(9, m, n)
+    out = oracle.server_epoch(z, perm_in)
+    ident = oracle.server_epoch(z)
+    for i in range(m):
+        assert sorted(out["perm"][i].tolist()) == list(range(n))
+        # composition: perm_out = perm_in o pi'
+        assert out["perm"][i].tolist() == perm_in[i][ident["perm"][i]].tolist()
+        eps = ident["eps"][i]
+        front = [2 * k + 1 if eps[k] == 1 else 2 * k for k in range(n // 2)]
+        back = [2 * k if eps[k] == 1 else 2 * k + 1 for k in range(n // 2)]
+        assert ident["perm"][i].tolist() == front + back[::-1]
+    # signs do not depend on perm_in (rows are already in visiting order)
+    assert out["eps"].tolist() == ident["eps"].tolist()
+
+
+def test_lemma1_prefix_identities():
+    """Proof of Lemma 1: with x+ / x- the +1 / -1 example of each pair,
+    sum_{k<=K} x+_{i,k} = (kappa_{i,K} + upsilon_{i,K})/2, sum_i upsilon_{i,K} is
+    the running sum after step K, and the new order visits x+_1..x+_{n/2} then
+    x-_{n/2}..x-_1."""
+    m, n, d = 3, 12, 6
+    z = workloads.integer_rows(21, m, n, d, 6)
+    out = oracle.server_epoch(z)
+    z64 = z.astype(np.float64)
+    # running sum after each step K from the block-fed form
+    r = np.zeros(d)
+    rows = _flatten_pairs(z)
+    for K in range(1, n // 2 + 1):
+        oracle.stream_pairs(r, rows[(K - 1) * m:K * m])
+        ups_total = np.zeros(d)
+        for i in range(m):
+            s1 = -out["eps"][i, :K].astype(np.float64)          # sign of the first row
+            first, second = z64[i, 0:2 * K:2], z64[i, 1:2 * K:2]
+            kappa = (first + second).sum(0)
+            ups = (s1[:, None] * first - s1[:, None] * second).sum(0)
+            ups_total += ups
+            new_order = out["perm"][i]
+            xplus = z64[i, new_order[:K]].sum(0)
+            xminus = z64[i, new_order[n - K:]].sum(0)
+            np.testing.assert_array_equal(xplus, 0.5 * (kappa + ups))
+            np.testing.assert_array_equal(xminus, 0.5 * (kappa - ups))
+        # paper: sum_i upsilon = sum_p s_p y_p with y = z1 - z2, which is the running sum
+        np.testing.assert_array_equal(ups_total, r)
+    np.testing.assert_array_equal(r, out["r"])
+
+
+def test_block_fed_form_and_replay():
+    m, n, d = 4, 16, 40
+    z = workloads.heavy_rows(3, m, n, d)
+    full = oracle.server_epoch(z)
+    rows = _flatten_pairs(z)
+    r = np.zeros(d)
+    eps_all, t_all = [], []
+    for start in range(0, rows.shape[0], 5):               # ragged blocks
+        eps, t, nr, nc = oracle.stream_pairs(r, rows[start:start + 5])
+        eps_all.append(eps)
+        t_all.append(t)
+    eps_all = np.concatenate(eps_all)
+    np.testing.assert_array_equal(eps_all, full["eps"].T.reshape(-1))
+    np.testing.assert_array_equal(r, full["r"])
+    np.testing.assert_array_equal(np.concatenate(t_all), full["t"].T.reshape(-1))
+    # replay with the same signs reproduces r; with one sign flipped it moves by 2 d_k
+    r2 = np.zeros(d)
+    oracle.stream_pairs(r2, rows, eps_in=eps_all)
+    np.testing.assert_array_equal(r2, r)
+    flipped = eps_all.copy()
+    flipped[7] = -flipped[7]
+    r3 = np.zeros(d)
+    eps3, t3, _, _ = oracle.stream_pairs(r3, rows, eps_in=flipped)
+    np.testing.assert_array_equal(eps3, flipped)
+    d7 = rows[7, 1].astype(np.float64) - rows[7, 0].astype(np.float64)
+    np.testing.assert_allclose(r3 - r, 2.0 * flipped[7] * d7, atol=1e-12)
+    assert t3[7] == t_all[1][2]                             # same state before pair 7
+
+
+# --------------------------------------------------------------------------- special cases
+def test_single_worker_is_centralized_pair_balance():
+    """m=1: the walk is the centralized online PairBalance (App. B.4): pairs in
+    order, one running sum.  Checked through the single-step routine."""
+    n, d = 10, 9
+    z = workloads.tiny_epoch(2, 1, n, d)
+    out = oracle.server_epoch(z)
+    r = np.zeros(d)
+    for k in range(n // 2):
+        c = z[0, 2 * k].astype(np.float64) - z[0, 2 * k + 1].astype(np.float64)
+        s, t, _, _ = oracle.greedy_balance(r, c)
+        assert out["eps"][0, k] == -s
+    np.testing.assert_array_equal(r, out["r"])
+
+
+def test_identical_rows_all_ties():
+    m, n, d = 3, 8, 5
+    z = np.tile(np.arange(d, dtype=np.float32), (m, n, 1))
+    out = oracle.server_epoch(z)
+    assert np.all(out["eps"] == 1)            # every dot is 0 -> tie rule -> eps=+1
+    assert np.all(out["r"] == 0)
+    want = list(range(1, n, 2)) + list(range(n - 2, -1, -2))
+    for i in range(m):
+        assert out["perm"][i].tolist() == want
+
+
+def test_power_of_two_scaling():
+    z = workloads.tiny_epoch(4, 3, 12, 33)
+    a = oracle.server_epoch(z)
+    b = oracle.server_epoch(z * np.float32(2.0 ** -7))
+    assert a["eps"].tolist() == b["eps"].tolist()
+    assert a["perm"].tolist() == b["perm"].tolist()
+    np.testing.assert_array_equal(a["r"] * 2.0 ** -7, b["r"])
+
+
+def test_first_pair_always_plus():
+    for seed in range(5):
+        z = workloads.tiny_epoch(seed, 2, 4, 7)
+        assert oracle.server_epoch(z)["eps"][0, 0] == 1     # r=0 -> tie -> eps=+1
+
+
+def test_rejects_odd_n():
+    with pytest.raises(ValueError):
+        oracle.server_epoch(np.zeros((2, 3, 4), np.float32))
+
+
+# --------------------------------------------------------------------------- reorder
+@pytest.mark.parametrize("signs,perm_in,expect", load_reorder_cases(os.path.join(GOLDEN, "reorder_cases.txt")))
+def test_reorder_hand_cases(signs, perm_in, expect):
+    assert oracle.reorder(signs, perm_in).tolist() == expect.tolist()
+
+
+def test_reorder_properties_random():
+    rng = np.random.default_rng(0)
+    for n in [1, 2, 3, 17, 64, 257]:
+        signs = (2 * rng.integers(0, 2, n) - 1).astype(np.int8)
+        perm_in = rng.permutation(n).astype(np.int32)
+        out = oracle.reorder(signs, perm_in)
+        assert sorted(out.tolist()) == list(range(n))
+        npos = int((signs == 1).sum())
+        assert out[:npos].tolist() == perm_in[signs == 1].tolist()
+        assert out[npos:].tolist() == perm_in[signs == -1][::-1].tolist()
+
+
+def test_reorder_rejects_bad_sign():
+    with pytest.raises(ValueError):
+        oracle.reorder(np.array([1, 0, -1], np.int8))
+
+
+def test_pair_pointer_form_equals_list_form():
+    """The pointer form (App. C.1) and the list form (Sec. 2.1) fed the expanded
+    signs (first row -eps, second row +eps) give the same order."""
+    m, n, d = 4, 14, 8
+    z = workloads.tiny_epoch(13, m, n, d)
+    perm_in = workloads.random_perms(14, m, n)
+    out = oracle.server_epoch(z, perm_in)
+    for i in range(m):
+        per_example = np.empty(n, np.int8)
+        per_example[0::2] = -out["eps"][i]
+        per_example[1::2] = out["eps"][i]
+        assert oracle.reorder(per_example, perm_in[i]).tolist() == out["perm"][i].tolist()
+
+
+# --------------------------------------------------------------------------- herding objective
+def test_parallel_herding_closed_form():
+    # two workers, d=1: z = [[1,-1],[2,-2]]: mean 0; prefix sums 3, 0 -> max 3
+    z = np.array([[[1.0], [-1.0]], [[2.0], [-2.0]]], np.float32)
+    assert oracle.parallel_herding(z) == 3.0
+    # visiting worker 2 in the other order: prefix sums 1-2=-1, 0 -> max 1
+    perm = np.array([[0, 1], [1, 0]], np.int32)
+    assert oracle.parallel_herding(z, perm) == 1.0
+    # un-centred vectors: mean is removed
+    assert oracle.parallel_herding(z + 5.0) == 3.0
+
+
+def test_reordering_lowers_herding_objective_on_average():
+    """Soft check of the purpose of the method (Lemma 1): over a few rounds of
+    balance+reorder on fixed vectors the parallel herding objective drops well
+    below that of the initial order."""
+    m, n, d = 4, 64, 16
+    rng = np.random.default_rng(1)
+    z = rng.random((m, n, d)).astype(np.float32)
+    perm = np.tile(np.arange(n, dtype=np.int32), (m, 1))
+    start = oracle.parallel_herding(z, perm)
+    for _ in range(6):
+        visited = np.stack([z[i, perm[i]] for i in range(m)])
+        perm = oracle.server_epoch(visited, perm)["perm"]
+    assert oracle.parallel_herding(z, perm) < 0.5 * start
+
+
+# --------------------------------------------------------------------------- per-example gradient
+def test_pergrad_finite_differences():
+    X, y, W = workloads.softmax_problem(0, 6, in_dim=7, classes=4)
+    W = (W * 30).astype(np.float32)                         # make the softmax non-uniform
+    G = oracle.softmax_pergrad(X, y, W)
+    W64 = W.astype(np.float64)
+    h = 1e-6
+    for e in range(X.shape[0]):
+        num = np.zeros_like(W64)
+        for idx in np.ndindex(*W64.shape):
+            Wp, Wm = W64.copy(), W64.copy()
+            Wp[idx] += h
+            Wm[idx] -= h
+            num[idx] = (oracle.softmax_loss(X[e], y[e], Wp) - oracle.softmax_loss(X[e], y[e], Wm)) / (2 * h)
+        np.testing.assert_allclose(G[e].reshape(W.shape), num, rtol=2e-5, atol=2e-7)
+
+
+def test_pergrad_structure_and_autograd():
+    import torch
+    X, y, W = workloads.softmax_problem(1, 16, in_dim=20, classes=10)
+    G = oracle.softmax_pergrad(X, y, W).reshape(16, 21, 10)
+    np.testing.assert_allclose(G.sum(2), 0, atol=1e-6)      # delta sums to zero
+    for e in range(16):
+        delta = G[e, 20]
+        np.testing.assert_allclose(G[e, :20], X[e][:, None] * delta[None, :], rtol=1e-6, atol=1e-9)
+        assert delta[y[e]] < 0 and np.all(np.delete(delta, y[e]) > 0)
+    Wt = torch.tensor(W, dtype=torch.float64, requires_grad=True)
+    for e in range(16):
+        xe = torch.cat([torch.tensor(X[e], dtype=torch.float64), torch.ones(1, dtype=torch.float64)])
+        loss = torch.nn.functional.cross_entropy((xe @ Wt)[None], torch.tensor([int(y[e])]))
+        g, = torch.autograd.grad(loss, Wt)
+        np.testing.assert_allclose(G[e], g.numpy(), rtol=1e-6, atol=1e-8)
+    # loss value itself against the library routine
+    l = oracle.softmax_loss(X[0], y[0], W.astype(np.float64))
+    xe = torch.cat([torch.tensor(X[0], dtype=torch.float64), torch.ones(1, dtype=torch.float64)])
+    ref = torch.nn.functional.cross_entropy((xe @ torch.tensor(W, dtype=torch.float64))[None],
+                                            torch.tensor([int(y[0])]))
+    assert abs(l - ref.item()) < 1e-12
+
+
+def test_pergrad_rejects_bad_label():
+    X, y, W = workloads.softmax_problem(2, 3, in_dim=4, classes=3)
+    y[1] = 3
+    with pytest.raises(ValueError):
+        oracle.softmax_pergrad(X, y, W)
