@@ -1,0 +1,167 @@
+/*
+ * cdgrab.h -- C ABI of the MI355X (gfx950) CD-GraB pair-balancing library.
+ *
+ * The library implements the order-server hot path of CD-GraB (arXiv 2302.00845):
+ * per-example gradients of m data-parallel workers -> pair differences ->
+ * coordinated greedy sign balancing on one running sum -> next-epoch
+ * permutations.  The m workers are a batch axis on one GPU.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked "dev" are device (HBM) addresses on the handle's device;
+ *     pointers marked "host" are ordinary host addresses.  The caller owns every
+ *     input and output buffer; inputs are never modified.  The handle owns its
+ *     workspace (running sum, partial results, staging block).
+ *   - Work is enqueued on the handle's HIP stream; a call returns once the work
+ *     is enqueued unless stated otherwise.  The caller synchronises the stream
+ *     before reading outputs.  Calls on one handle must not overlap.
+ *   - Return value: CDGRAB_OK (0) or a negative error code.  After an error the
+ *     contents of the outputs are undefined; cdgrab_last_error() gives a text.
+ *   - Sizes are int64_t counts of elements, never bytes.
+ */
+#ifndef CDGRAB_H
+#define CDGRAB_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CDGRAB_OK 0
+#define CDGRAB_EINVAL (-1) /* bad size, null required pointer, odd n, bad option   */
+#define CDGRAB_ENOMEM (-2) /* workspace allocation failed                           */
+#define CDGRAB_EHIP (-3)   /* a HIP runtime call failed (text in last_error)        */
+#define CDGRAB_EGEN (-4)   /* the generator callback returned non-zero              */
+
+typedef struct cdgrab_handle cdgrab_handle;
+
+typedef struct cdgrab_options {
+    int32_t device;      /* HIP device ordinal                                        */
+    int32_t block_pairs; /* Bb: pairs resolved per HBM pass; 0 = choose, else 16 or 32 */
+    void *stream;        /* hipStream_t to enqueue on; NULL = the null stream         */
+    int32_t timing;      /* 0 off; 1 record events around generator / balancer work;
+                            2 additionally around every balancer kernel               */
+    int32_t pass1_groups; /* workgroups of the dot/Gram pass; 0 = choose              */
+} cdgrab_options;
+
+/* Event-timed durations of the last cdgrab_balance_epoch call (timing >= 1);
+ * the per-kernel fields are filled only with timing == 2.  Milliseconds. */
+typedef struct cdgrab_timing {
+    double generator_ms; /* time inside the generator callback's enqueued work */
+    double balance_ms;   /* dot/Gram pass + reduce + resolve + apply pass, all blocks */
+    double pass1_ms;     /* dot/Gram pass, summed over blocks                  */
+    double reduce_ms;    /* partial reduction                                  */
+    double resolve_ms;   /* sequential sign resolution                         */
+    double pass2_ms;     /* apply pass                                         */
+    double finish_ms;    /* permutation build + running-sum export             */
+    int64_t blocks;      /* number of blocks processed                         */
+    int32_t block_pairs; /* Bb used                                            */
+    int32_t pass1_groups;/* workgroups used by the dot/Gram pass               */
+} cdgrab_timing;
+
+/* How one epoch is cut into blocks (pure host arithmetic; needs no GPU). */
+typedef struct cdgrab_plan {
+    int64_t pairs;           /* m*n/2 flattened pair differences                      */
+    int64_t blocks;          /* ceil(pairs / block_pairs)                             */
+    int32_t block_pairs;     /* Bb                                                    */
+    int32_t vector_width;    /* fp32 elements per global load: 4, 2 or 1              */
+    int32_t pass1_groups;    /* workgroups of the dot/Gram pass                       */
+    int32_t pass2_groups;    /* workgroups of the apply pass                          */
+    int64_t workspace_bytes; /* running sum + partials (+ staging when streaming)     */
+    int64_t staging_bytes;   /* one staging block [Bb][2][d] fp32, 0 for dense input  */
+    double bytes_per_example;/* algorithmic HBM bytes per example: 8d + 12 d / Bb     */
+} cdgrab_plan;
+
+/* Generator callback for streamed input ("grads-or-generator").  It must enqueue,
+ * on `stream`, work that fills staging[count][2][d] (fp32, dev) with the rows of
+ * the flattened pairs first_pair .. first_pair+count-1: staging[q][0] is the
+ * first row the worker visited of pair first_pair+q, staging[q][1] the second.
+ * Flattened pair p belongs to worker p % m and is that worker's pair p / m
+ * (step-major, worker-minor: the order in which the server algorithm of
+ * Sec. 3.3 / App. C.1 visits pairs).  Return 0 on success. */
+typedef int (*cdgrab_gen_fn)(void *ctx, int64_t first_pair, int64_t count,
+                             float *staging /*dev*/, void *stream);
+
+/* Create / destroy a handle.  `opt` may be NULL (device 0, null stream, automatic
+ * block size, no timing).  Allocates nothing until the first call that needs
+ * workspace.  Errors: EINVAL (bad option), EHIP (no such device). */
+int cdgrab_create(cdgrab_handle **out, const cdgrab_options *opt);
+int cdgrab_destroy(cdgrab_handle *h);
+
+/* Text of the last error on this handle (owned by the handle, valid until the
+ * next call on it).  With h == NULL: the text of the last failed cdgrab_create. */
+const char *cdgrab_last_error(const cdgrab_handle *h);
+
+/* Blocking plan for an epoch of m workers x n rows x d parameters.  `streamed`
+ * non-zero means rows come from a generator.  block_pairs 0 = automatic.
+ * `base_align` is the byte alignment of the gradient base pointer (16 if unknown
+ * allocations come from hipMalloc).  Host only.  Errors: EINVAL. */
+int cdgrab_plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs,
+                      int32_t streamed, int64_t base_align, cdgrab_plan *plan /*host*/);
+
+/* Per-example gradients of softmax cross-entropy for a linear model: the vector a
+ * worker sends for each example ("CD-GraB Workers", line 4; per-example gradients
+ * as in footnote 2 of Sec. 2).
+ *   X [N][in_dim] fp32 dev, y [N] int32 dev (0 <= y < classes, not checked),
+ *   W [(in_dim+1)][classes] fp32 dev, last row is the bias,
+ *   G_out [N][(in_dim+1)*classes] fp32 dev:
+ *     delta = softmax(W^T [x;1]) - onehot(y);
+ *     G_out[e][r*classes + c] = x_r * delta_c,  G_out[e][in_dim*classes + c] = delta_c.
+ * fp32 arithmetic.  Errors: EINVAL (N<0, in_dim<1, classes<1 or >1024, null). */
+int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
+                   const float *X, const int32_t *y, const float *W, float *G_out);
+
+/* One epoch of coordinated pair balancing (server algorithm of Sec. 3.3, lines
+ * 3-14; one-step form App. C.1) with the deterministic greedy rule of App. B.2
+ * ("Balancing without normalization").
+ *
+ *   running sum r = 0
+ *   for pair k = 0 .. n/2-1, worker i = 0 .. m-1 (in this order):
+ *       dvec = row(i, 2k+1) - row(i, 2k)          (second minus first)
+ *       t    = <r, dvec>
+ *       eps  = +1 if t <= 0 else -1               (the paper's sign for the first
+ *                                                  row is -eps; a zero dot gives +1)
+ *       r   += eps * dvec
+ *   per worker: the row with sign +1 of each pair goes to the front list in pair
+ *   order, the other to the back list, which is reversed:
+ *       pi'[k] = 2k+1 if eps==+1 else 2k;  pi'[n-1-k] = the other;
+ *       perm_out[i][p] = perm_in[i][pi'[p]]       (pi' itself if perm_in is NULL)
+ *
+ * Inputs: either `grads` [m][n][d] fp32 dev (row (i,j) = the j-th gradient worker i
+ * produced this epoch) or, with grads == NULL, a generator callback that fills a
+ * staging block owned by the handle.  Exactly one of the two must be given.
+ *   perm_in   [m][n] int32 dev or NULL : example id at each visiting position
+ *   signs_out [m][n/2] int8 dev        : eps per (worker, pair)
+ *   perm_out  [m][n] int32 dev         : next epoch's order
+ *   r_out     [d] fp32 dev or NULL     : final running sum, rounded from double
+ *   r64_out   [d] fp64 dev or NULL     : final running sum in double
+ *   dots_out  [m][n/2] fp64 dev or NULL: t seen when each pair was decided
+ * Arithmetic: differences, dots, Gram entries and the running sum are IEEE double
+ * (fp32 inputs); sums over d are taken in a fixed order, so results are
+ * reproducible run to run.
+ * Errors: EINVAL (m<1, n<2, n odd, d<1, null required pointer, both or neither of
+ * grads / gen), ENOMEM, EHIP, EGEN. */
+int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
+                         const float *grads, cdgrab_gen_fn gen, void *gen_ctx,
+                         const int32_t *perm_in, int8_t *signs_out,
+                         int32_t *perm_out, float *r_out, double *r64_out,
+                         double *dots_out);
+
+/* Reorder from arbitrary per-example signs ("Reordering Vectors based on Balanced
+ * Signs", Sec. 2.1), one independent problem per worker:
+ *   perm_out[i] = concat(L_pos, reverse(L_neg)), L_pos / L_neg the entries of
+ *   perm_in[i] (identity if NULL) whose sign is +1 / -1, in visiting order.
+ *   signs [m][n] int8 dev, perm_in [m][n] int32 dev or NULL, perm_out [m][n] int32 dev.
+ * This call synchronises the stream to report a sign that is not +1 or -1.
+ * Errors: EINVAL (m<1, n<1, null pointer, bad sign value), EHIP. */
+int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,
+                   const int32_t *perm_in, int32_t *perm_out);
+
+/* Timings of the last cdgrab_balance_epoch on this handle (options.timing >= 1).
+ * Synchronises the stream.  Errors: EINVAL (timing was off), EHIP. */
+int cdgrab_get_timing(cdgrab_handle *h, cdgrab_timing *out /*host*/);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CDGRAB_H */

@@ -1,0 +1,356 @@
+// Blocked pair-balancing kernels for gfx950 (CDNA4).
+//
+// The greedy walk of CD-GraB (App. B.2 "Balancing without normalization" applied
+// pair by pair in the server algorithm's order, Sec. 3.3) decides each sign from
+// <r, d_k>, where r already contains the earlier differences.  For a block of Bb
+// consecutive differences
+//     <r + sum_{j<k} eps_j d_j, d_k> = <r, d_k> + sum_{j<k} eps_j <d_j, d_k>,
+// so one pass over the rows yields everything the Bb decisions need: the Bb dots
+// with the block-start running sum and the Bb x Bb Gram matrix.  A single
+// wavefront then resolves the signs in order, and a second pass applies
+// r += sum_k eps_k d_k.  Each gradient row is read from HBM twice per epoch.
+//
+// Arithmetic: rows are fp32; differences are formed in double (exact), dots with
+// r are double FMAs, the Gram matrix is accumulated by the double-precision MFMA
+// (products of two exact fp32 differences are exact in double), and all
+// cross-lane / cross-workgroup sums are taken in a fixed order.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cdgrab {
+
+constexpr int kThreads = 256;       // workgroup size of the streaming kernels
+constexpr int kWaves = kThreads / 64;
+constexpr int kTileE = 64;          // elements of d per LDS tile
+constexpr int kLdsStride = kTileE + 4;  // floats per LDS row (16 B aligned, bank-skewed)
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
+// Where the rows of the current block live.  Flattened pair p = p0 + j belongs to
+// worker p % m and is that worker's pair p / m.  Dense input is [m][n][d]; a
+// staging block is [Bb][2][d].
+struct RowMap {
+    const float *base;
+    int64_t d;
+    int64_t p0;
+    int64_t m;
+    int64_t n;
+    int32_t dense;  // 1: base is the caller's [m][n][d] array; 0: base is a staging block
+    int32_t nb;     // valid pairs in this block (<= Bb)
+
+    __device__ __forceinline__ const float *row(int j, int which) const {
+        if (dense) {
+            int64_t p = p0 + j;
+            int64_t k = p / m;
+            int64_t i = p - k * m;
+            return base + ((i * n) + 2 * k + which) * d;
+        }
+        return base + (int64_t)(2 * j + which) * d;
+    }
+};
+
+// Four consecutive fp32 elements starting at element e of a row, zero beyond d.
+// VW is the widest load the row alignment allows (4, 2 or 1 floats).
+template <int VW>
+__device__ __forceinline__ float4 load4(const float *row, int64_t e, int64_t d) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (row == nullptr) return v;
+    if constexpr (VW == 4) {
+        if (e < d) v = *reinterpret_cast<const float4 *>(row + e);
+    } else if constexpr (VW == 2) {
+        if (e < d) { float2 t = *reinterpret_cast<const float2 *>(row + e); v.x = t.x; v.y = t.y; }
+        if (e + 2 < d) { float2 t = *reinterpret_cast<const float2 *>(row + e + 2); v.z = t.x; v.w = t.y; }
+    } else {
+        if (e < d) v.x = row[e];
+        if (e + 1 < d) v.y = row[e + 1];
+        if (e + 2 < d) v.z = row[e + 2];
+        if (e + 3 < d) v.w = row[e + 3];
+    }
+    return v;
+}
+
+// Number of doubles one workgroup of the dot/Gram pass emits: the Gram tiles in
+// the MFMA accumulator layout (tile * 256 + v * 64 + lane) followed by Bb dots.
+template <int BB> struct PartLayout {
+    static constexpr int RG = BB / 16;               // 16-row groups
+    static constexpr int NT = RG * (RG + 1) / 2;     // upper-triangular 16x16 tiles
+    static constexpr int GRAM = NT * 256;
+    static constexpr int PART = GRAM + BB;
+};
+
+// Row / column of accumulator element v of lane `lane` in the 16x16 result of
+// v_mfma_f64_16x16x4_f64: column = lane % 16, row = 4 * v + lane / 16
+// (measured on gfx950 with a rank-one probe).
+__device__ __forceinline__ void mfma_f64_16x16_coord(int lane, int v, int &i, int &j) {
+    j = lane & 15;
+    i = 4 * v + (lane >> 4);
+}
+
+// ---------------------------------------------------------------------------
+// Pass 1: partial dots <r, d_k> and partial Gram <d_j, d_k> over a strided set
+// of 64-element tiles of d.  One workgroup = 4 waves; each tile is staged
+// through LDS (coalesced 16 B global loads -> row-per-lane MFMA operands).
+// Lane (row = lane % 16, kslot = lane / 16) of wave w owns elements
+// 16 w + 4 kslot .. +3 of the tile for pair `row` of each 16-pair group.
+template <int BB, int VW>
+__global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const double *__restrict__ r_sum,
+                                                            double *__restrict__ partials,
+                                                            int64_t ntiles)
+{
+    using L = PartLayout<BB>;
+    constexpr int RG = L::RG;
+    constexpr int LOADS = 2 * BB / 16;  // 16 B loads per thread per tile
+    constexpr int TILE_FLOATS = BB * kLdsStride;
+    // LDS: two stages of (first rows, second rows, running-sum chunk); the final
+    // cross-wave reduction reuses the same bytes.
+    constexpr int STAGE_BYTES = 2 * TILE_FLOATS * 4 + kTileE * 8;
+    constexpr int RED_BYTES = kWaves * (L::GRAM + RG * 64) * 8;
+    constexpr int SMEM = (2 * STAGE_BYTES > RED_BYTES) ? 2 * STAGE_BYTES : RED_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int64_t d = rm.d;
+
+    // global -> register mapping: 16 threads cover one row's 64 elements
+    const int lrow = tid >> 4;
+    const int chunk = tid & 15;
+    const float *src[LOADS];
+    int lds_off[LOADS];
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u) {
+        int rr = u * 16 + lrow;        // 0 .. 2*BB-1
+        int j = rr >> 1, which = rr & 1;
+        src[u] = (j < rm.nb) ? rm.row(j, which) : nullptr;
+        lds_off[u] = (which * TILE_FLOATS + j * kLdsStride + chunk * 4) * 4;
+    }
+
+    double4_t acc[L::NT];
+#pragma unroll
+    for (int q = 0; q < L::NT; ++q) acc[q] = (double4_t){0.0, 0.0, 0.0, 0.0};
+    double pdot[RG];
+#pragma unroll
+    for (int g = 0; g < RG; ++g) pdot[g] = 0.0;
+
+    const int mrow = lane & 15;
+    const int kslot = lane >> 4;
+    const int eo = 16 * wave + 4 * kslot;  // element offset inside the tile
+
+    float4 stage_regs[LOADS];
+    double2 stage_s = make_double2(0.0, 0.0);
+
+    int64_t tile = blockIdx.x;
+    if (tile < ntiles) {
+#pragma unroll
+        for (int u = 0; u < LOADS; ++u) stage_regs[u] = load4<VW>(src[u], tile * kTileE + chunk * 4, d);
+        if (tid < kTileE / 2) stage_s = *reinterpret_cast<const double2 *>(r_sum + tile * kTileE + tid * 2);
+    }
+    int buf = 0;
+    for (; tile < ntiles; tile += gridDim.x) {
+        unsigned char *stage = smem + buf * STAGE_BYTES;
+#pragma unroll
+        for (int u = 0; u < LOADS; ++u)
+            *reinterpret_cast<float4 *>(stage + lds_off[u]) = stage_regs[u];
+        if (tid < kTileE / 2)
+            *reinterpret_cast<double2 *>(stage + 2 * TILE_FLOATS * 4 + tid * 16) = stage_s;
+        __syncthreads();
+
+        // prefetch the next tile while this one is consumed
+        int64_t nxt = tile + gridDim.x;
+        if (nxt < ntiles) {
+#pragma unroll
+            for (int u = 0; u < LOADS; ++u) stage_regs[u] = load4<VW>(src[u], nxt * kTileE + chunk * 4, d);
+            if (tid < kTileE / 2) stage_s = *reinterpret_cast<const double2 *>(r_sum + nxt * kTileE + tid * 2);
+        }
+
+        const float *first = reinterpret_cast<const float *>(stage);
+        const float *second = first + TILE_FLOATS;
+        const double *sv = reinterpret_cast<const double *>(stage + 2 * TILE_FLOATS * 4);
+        float4 a[RG], b[RG];
+#pragma unroll
+        for (int g = 0; g < RG; ++g) {
+            a[g] = *reinterpret_cast<const float4 *>(first + (16 * g + mrow) * kLdsStride + eo);
+            b[g] = *reinterpret_cast<const float4 *>(second + (16 * g + mrow) * kLdsStride + eo);
+        }
+        double2 s01 = *reinterpret_cast<const double2 *>(sv + eo);
+        double2 s23 = *reinterpret_cast<const double2 *>(sv + eo + 2);
+        const double se[4] = {s01.x, s01.y, s23.x, s23.y};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            double dd[RG];
+#pragma unroll
+            for (int g = 0; g < RG; ++g) {
+                float fa = (t == 0) ? a[g].x : (t == 1) ? a[g].y : (t == 2) ? a[g].z : a[g].w;
+                float fb = (t == 0) ? b[g].x : (t == 1) ? b[g].y : (t == 2) ? b[g].z : b[g].w;
+                dd[g] = (double)fb - (double)fa;
+                pdot[g] = __builtin_fma(se[t], dd[g], pdot[g]);
+            }
+            // upper-triangular tiles, row group g (A operand) x row group h >= g (B operand)
+            int q = 0;
+#pragma unroll
+            for (int g = 0; g < RG; ++g)
+#pragma unroll
+                for (int h = g; h < RG; ++h) {
+                    acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(dd[g], dd[h], acc[q], 0, 0, 0);
+                    ++q;
+                }
+        }
+        buf ^= 1;
+    }
+
+    // cross-wave reduction in a fixed order
+    __syncthreads();
+    double *red = reinterpret_cast<double *>(smem);
+    constexpr int PER_WAVE = L::GRAM + RG * 64;
+#pragma unroll
+    for (int q = 0; q < L::NT; ++q)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[wave * PER_WAVE + q * 256 + v * 64 + lane] = acc[q][v];
+#pragma unroll
+    for (int g = 0; g < RG; ++g) red[wave * PER_WAVE + L::GRAM + g * 64 + lane] = pdot[g];
+    __syncthreads();
+    double *out = partials + (int64_t)blockIdx.x * L::PART;
+    for (int idx = tid; idx < L::GRAM; idx += kThreads) {
+        double sum = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) sum += red[w * PER_WAVE + idx];
+        out[idx] = sum;
+    }
+    if (tid < BB) {
+        int g = tid >> 4, rw = tid & 15;
+        double sum = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) sum += red[w * PER_WAVE + L::GRAM + g * 64 + ks * 16 + rw];
+        out[L::GRAM + tid] = sum;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Fixed-order reduction of the per-workgroup partials: 32 entries per workgroup,
+// 8 segments of the partial list per entry, segments combined in order.
+constexpr int kReduceEntries = 32;
+constexpr int kReduceSegs = kThreads / kReduceEntries;
+
+__global__ __launch_bounds__(kThreads) void reduce_partials(const double *__restrict__ partials,
+                                                            double *__restrict__ reduced, int part,
+                                                            int groups)
+{
+    __shared__ double segsum[kReduceSegs][kReduceEntries];
+    const int ent = threadIdx.x % kReduceEntries;
+    const int seg = threadIdx.x / kReduceEntries;
+    const int entry = blockIdx.x * kReduceEntries + ent;
+    const int g0 = (int)((int64_t)seg * groups / kReduceSegs);
+    const int g1 = (int)((int64_t)(seg + 1) * groups / kReduceSegs);
+    double sum = 0.0;
+    if (entry < part)
+        for (int g = g0; g < g1; ++g) sum += partials[(int64_t)g * part + entry];
+    segsum[seg][ent] = sum;
+    __syncthreads();
+    if (seg == 0 && entry < part) {
+        double tot = 0.0;
+#pragma unroll
+        for (int q = 0; q < kReduceSegs; ++q) tot += segsum[q][ent];
+        reduced[entry] = tot;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Sequential sign resolution by one wavefront.  Lane k carries
+// t_k = <r, d_k> + sum_{j<k, decided} eps_j G[j][k]; step j broadcasts t_j,
+// fixes eps_j = +1 if t_j <= 0 else -1 and updates the later lanes.
+template <int BB>
+__global__ __launch_bounds__(64) void resolve_signs(const double *__restrict__ reduced, int nb,
+                                                    int64_t p0, int64_t m, int64_t half_n,
+                                                    int8_t *__restrict__ eps_blk,
+                                                    int8_t *__restrict__ signs_out,
+                                                    double *__restrict__ dots_out)
+{
+    using L = PartLayout<BB>;
+    __shared__ double G[BB][BB + 1];
+    const int lane = threadIdx.x;
+    for (int idx = lane; idx < L::GRAM; idx += 64) {
+        int tile = idx >> 8, v = (idx >> 6) & 3, ln = idx & 63;
+        int i, j;
+        mfma_f64_16x16_coord(ln, v, i, j);
+        double val = reduced[idx];
+        if (L::RG == 1) {
+            G[i][j] = val;
+        } else {
+            // tiles in order (0,0), (0,1), (1,1)
+            if (tile == 0) G[i][j] = val;
+            else if (tile == 1) { G[i][16 + j] = val; G[16 + j][i] = val; }
+            else G[16 + i][16 + j] = val;
+        }
+    }
+    __syncthreads();
+    double t = (lane < nb) ? reduced[L::GRAM + lane] : 0.0;
+    for (int j = 0; j < nb; ++j) {
+        double tj = __shfl(t, j, 64);
+        int eps = (tj <= 0.0) ? 1 : -1;
+        if (lane == j) {
+            int64_t p = p0 + j;
+            int64_t k = p / m, i = p - k * m;
+            eps_blk[j] = (int8_t)eps;
+            signs_out[i * half_n + k] = (int8_t)eps;
+            if (dots_out) dots_out[i * half_n + k] = tj;
+        }
+        if (lane > j && lane < nb) t += (double)eps * G[j][lane];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Pass 2: r += sum_k eps_k d_k.  Each thread owns four consecutive elements and
+// streams the block's rows through registers.
+template <int BB, int VW>
+__global__ __launch_bounds__(kThreads) void pass2_apply(RowMap rm, const int8_t *__restrict__ eps_blk,
+                                                        double *__restrict__ r_sum)
+{
+    const int64_t d = rm.d;
+    const int64_t e = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+    if (e >= d) return;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll 8
+    for (int j = 0; j < BB; ++j) {
+        if (j < rm.nb) {
+            float4 a = load4<VW>(rm.row(j, 0), e, d);
+            float4 b = load4<VW>(rm.row(j, 1), e, d);
+            double sg = (double)eps_blk[j];
+            acc[0] = __builtin_fma(sg, (double)b.x - (double)a.x, acc[0]);
+            acc[1] = __builtin_fma(sg, (double)b.y - (double)a.y, acc[1]);
+            acc[2] = __builtin_fma(sg, (double)b.z - (double)a.z, acc[2]);
+            acc[3] = __builtin_fma(sg, (double)b.w - (double)a.w, acc[3]);
+        }
+    }
+    // the running sum is padded to a multiple of the tile; the padding stays zero
+    // because elements beyond d load as zero
+    double2 lo = *reinterpret_cast<double2 *>(r_sum + e);
+    double2 hi = *reinterpret_cast<double2 *>(r_sum + e + 2);
+    lo.x += acc[0]; lo.y += acc[1]; hi.x += acc[2]; hi.y += acc[3];
+    *reinterpret_cast<double2 *>(r_sum + e) = lo;
+    *reinterpret_cast<double2 *>(r_sum + e + 2) = hi;
+}
+
+// ---------------------------------------------------------------------------
+__global__ void fill_zero_f64(double *p, int64_t count) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) p[i] = 0.0;
+}
+
+__global__ void export_running_sum(const double *__restrict__ r_sum, int64_t d, float *__restrict__ r32,
+                                   double *__restrict__ r64)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < d; i += stride) {
+        double v = r_sum[i];
+        if (r32) r32[i] = (float)v;
+        if (r64) r64[i] = v;
+    }
+}
+
+}  // namespace cdgrab

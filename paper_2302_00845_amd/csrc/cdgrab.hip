@@ -1,0 +1,397 @@
+// C ABI of the CD-GraB pair-balancing library (see include/cdgrab.h for the
+// contract of every entry point).  Host orchestration only: every arithmetic
+// step of the path runs in the kernels of balance_kernels.hpp / order_kernels.hpp.
+#include "../../include/cdgrab.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "balance_kernels.hpp"
+#include "order_kernels.hpp"
+
+using namespace cdgrab;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+enum Interval { kGen = 0, kBalance, kPass1, kReduce, kResolve, kPass2, kFinish, kIntervalKinds };
+
+struct Mark {
+    hipEvent_t ev;
+    int kind_after;  // what runs between this mark and the next one (-1: nothing timed)
+};
+
+}  // namespace
+
+struct cdgrab_handle {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    int block_pairs_opt = 0;
+    int timing = 0;
+    int pass1_groups_opt = 0;
+    int num_cu = 256;
+    std::string err;
+
+    double *r_sum = nullptr;   int64_t r_cap = 0;         // doubles
+    double *partials = nullptr; int64_t partials_cap = 0; // doubles
+    double *reduced = nullptr;                            // PartLayout<32>::PART doubles
+    int8_t *eps_blk = nullptr;                            // 32 signs
+    int32_t *flag = nullptr;                              // reorder's bad-sign flag
+    float *staging = nullptr;  int64_t staging_cap = 0;   // floats
+
+    std::vector<hipEvent_t> event_pool;
+    std::vector<Mark> marks;
+    size_t events_used = 0;
+    bool have_timing = false;
+    cdgrab_timing last{};
+};
+
+namespace {
+
+int fail(cdgrab_handle *h, int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (h) h->err = buf; else g_create_error = buf;
+    return code;
+}
+
+#define HIP_TRY(h, expr)                                                                  \
+    do {                                                                                  \
+        hipError_t e_ = (expr);                                                           \
+        if (e_ != hipSuccess)                                                             \
+            return fail(h, CDGRAB_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));   \
+    } while (0)
+
+int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
+
+int pick_vector_width(int64_t d, int64_t base_align) {
+    if (d % 4 == 0 && base_align % 16 == 0) return 4;
+    if (d % 2 == 0 && base_align % 8 == 0) return 2;
+    return 1;
+}
+
+int pick_block_pairs(int64_t pairs, int32_t requested) {
+    if (requested == 16 || requested == 32) return requested;
+    return pairs > 16 ? 32 : 16;
+}
+
+int part_size(int bb) { return bb == 32 ? PartLayout<32>::PART : PartLayout<16>::PART; }
+
+int plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs, int32_t streamed,
+               int64_t base_align, int num_cu, int32_t pass1_groups_opt, cdgrab_plan *plan) {
+    if (m < 1 || n < 2 || (n & 1) || d < 1 || !plan) return CDGRAB_EINVAL;
+    if (block_pairs != 0 && block_pairs != 16 && block_pairs != 32) return CDGRAB_EINVAL;
+    if (base_align < 4 || (base_align & (base_align - 1))) return CDGRAB_EINVAL;
+    if (m > (INT64_MAX / n) / d) return CDGRAB_EINVAL;
+    plan->pairs = m * (n / 2);
+    plan->block_pairs = pick_block_pairs(plan->pairs, block_pairs);
+    plan->blocks = (plan->pairs + plan->block_pairs - 1) / plan->block_pairs;
+    plan->vector_width = pick_vector_width(d, streamed ? 256 : base_align);
+    int64_t ntiles = (d + kTileE - 1) / kTileE;
+    int64_t want = pass1_groups_opt > 0 ? pass1_groups_opt : (int64_t)num_cu * 4;
+    plan->pass1_groups = (int32_t)std::max<int64_t>(1, std::min<int64_t>(want, ntiles));
+    plan->pass2_groups = (int32_t)((d + kThreads * 4 - 1) / (kThreads * 4));
+    plan->staging_bytes = streamed ? (int64_t)plan->block_pairs * 2 * d * 4 : 0;
+    plan->workspace_bytes = round_up(d, kTileE) * 8 +
+                            (int64_t)plan->pass1_groups * part_size(plan->block_pairs) * 8 +
+                            plan->staging_bytes;
+    plan->bytes_per_example = 8.0 * (double)d + 12.0 * (double)d / plan->block_pairs;
+    return CDGRAB_OK;
+}
+
+// ---- timing marks ----------------------------------------------------------
+int mark(cdgrab_handle *h, int kind_after) {
+    if (h->events_used == h->event_pool.size()) {
+        hipEvent_t ev;
+        HIP_TRY(h, hipEventCreate(&ev));
+        h->event_pool.push_back(ev);
+    }
+    hipEvent_t ev = h->event_pool[h->events_used++];
+    HIP_TRY(h, hipEventRecord(ev, h->stream));
+    h->marks.push_back({ev, kind_after});
+    return CDGRAB_OK;
+}
+
+#define MARK(h, level, kind)                                   \
+    do {                                                       \
+        if ((h)->timing >= (level)) {                          \
+            int rc_ = mark((h), (kind));                       \
+            if (rc_ != CDGRAB_OK) return rc_;                  \
+        }                                                      \
+    } while (0)
+
+template <typename T>
+int ensure(cdgrab_handle *h, T *&ptr, int64_t &cap, int64_t want) {
+    if (cap >= want) return CDGRAB_OK;
+    if (ptr) { HIP_TRY(h, hipStreamSynchronize(h->stream)); HIP_TRY(h, hipFree(ptr)); ptr = nullptr; cap = 0; }
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&ptr), (size_t)want * sizeof(T));
+    if (e != hipSuccess) {
+        ptr = nullptr;
+        (void)hipGetLastError();
+        return fail(h, CDGRAB_ENOMEM, "workspace allocation of %lld bytes failed: %s",
+                    (long long)(want * (int64_t)sizeof(T)), hipGetErrorString(e));
+    }
+    cap = want;
+    return CDGRAB_OK;
+}
+
+template <int BB, int VW>
+void launch_pass1(cdgrab_handle *h, const RowMap &rm, int groups, int64_t ntiles) {
+    hipLaunchKernelGGL((pass1_dots_gram<BB, VW>), dim3(groups), dim3(kThreads), 0, h->stream, rm,
+                       h->r_sum, h->partials, ntiles);
+}
+template <int BB, int VW>
+void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
+    hipLaunchKernelGGL((pass2_apply<BB, VW>), dim3(groups), dim3(kThreads), 0, h->stream, rm,
+                       h->eps_blk, h->r_sum);
+}
+template <int BB>
+void launch_resolve(cdgrab_handle *h, const RowMap &rm, int8_t *signs_out, double *dots_out) {
+    hipLaunchKernelGGL((resolve_signs<BB>), dim3(1), dim3(64), 0, h->stream, h->reduced, rm.nb,
+                       rm.p0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out);
+}
+
+template <int BB>
+int run_block_vw(cdgrab_handle *h, const RowMap &rm, const cdgrab_plan &plan, int8_t *signs_out,
+                 double *dots_out) {
+    const int64_t ntiles = (rm.d + kTileE - 1) / kTileE;
+    const int part = PartLayout<BB>::PART;
+    MARK(h, 2, kPass1);
+    switch (plan.vector_width) {
+        case 4: launch_pass1<BB, 4>(h, rm, plan.pass1_groups, ntiles); break;
+        case 2: launch_pass1<BB, 2>(h, rm, plan.pass1_groups, ntiles); break;
+        default: launch_pass1<BB, 1>(h, rm, plan.pass1_groups, ntiles); break;
+    }
+    MARK(h, 2, kReduce);
+    hipLaunchKernelGGL(reduce_partials, dim3((part + kReduceEntries - 1) / kReduceEntries),
+                       dim3(kThreads), 0, h->stream, h->partials, h->reduced, part,
+                       plan.pass1_groups);
+    MARK(h, 2, kResolve);
+    launch_resolve<BB>(h, rm, signs_out, dots_out);
+    MARK(h, 2, kPass2);
+    switch (plan.vector_width) {
+        case 4: launch_pass2<BB, 4>(h, rm, plan.pass2_groups); break;
+        case 2: launch_pass2<BB, 2>(h, rm, plan.pass2_groups); break;
+        default: launch_pass2<BB, 1>(h, rm, plan.pass2_groups); break;
+    }
+    HIP_TRY(h, hipGetLastError());
+    return CDGRAB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cdgrab_create(cdgrab_handle **out, const cdgrab_options *opt) {
+    if (!out) return fail(nullptr, CDGRAB_EINVAL, "cdgrab_create: out is NULL");
+    *out = nullptr;
+    cdgrab_options o{};
+    if (opt) o = *opt;
+    if (o.block_pairs != 0 && o.block_pairs != 16 && o.block_pairs != 32)
+        return fail(nullptr, CDGRAB_EINVAL, "block_pairs must be 0, 16 or 32 (got %d)", o.block_pairs);
+    if (o.timing < 0 || o.timing > 2) return fail(nullptr, CDGRAB_EINVAL, "timing must be 0, 1 or 2");
+    if (o.pass1_groups < 0 || o.pass1_groups > 65536)
+        return fail(nullptr, CDGRAB_EINVAL, "pass1_groups out of range");
+    int count = 0;
+    hipError_t e = hipGetDeviceCount(&count);
+    if (e != hipSuccess || o.device < 0 || o.device >= count)
+        return fail(nullptr, CDGRAB_EHIP, "no HIP device %d (%d visible): %s", o.device, count,
+                    hipGetErrorString(e));
+    cdgrab_handle *h = new (std::nothrow) cdgrab_handle();
+    if (!h) return fail(nullptr, CDGRAB_ENOMEM, "out of host memory");
+    h->device = o.device;
+    h->stream = reinterpret_cast<hipStream_t>(o.stream);
+    h->block_pairs_opt = o.block_pairs;
+    h->timing = o.timing;
+    h->pass1_groups_opt = o.pass1_groups;
+    hipDeviceProp_t prop;
+    if (hipSetDevice(h->device) == hipSuccess && hipGetDeviceProperties(&prop, h->device) == hipSuccess)
+        h->num_cu = prop.multiProcessorCount;
+    *out = h;
+    return CDGRAB_OK;
+}
+
+int cdgrab_destroy(cdgrab_handle *h) {
+    if (!h) return CDGRAB_OK;
+    (void)hipSetDevice(h->device);
+    (void)hipStreamSynchronize(h->stream);
+    for (hipEvent_t ev : h->event_pool) (void)hipEventDestroy(ev);
+    if (h->r_sum) (void)hipFree(h->r_sum);
+    if (h->partials) (void)hipFree(h->partials);
+    if (h->reduced) (void)hipFree(h->reduced);
+    if (h->eps_blk) (void)hipFree(h->eps_blk);
+    if (h->flag) (void)hipFree(h->flag);
+    if (h->staging) (void)hipFree(h->staging);
+    delete h;
+    return CDGRAB_OK;
+}
+
+const char *cdgrab_last_error(const cdgrab_handle *h) {
+    return h ? h->err.c_str() : g_create_error.c_str();
+}
+
+int cdgrab_plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs, int32_t streamed,
+                      int64_t base_align, cdgrab_plan *plan) {
+    return plan_epoch(m, n, d, block_pairs, streamed, base_align, 256, 0, plan);
+}
+
+int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes, const float *X,
+                   const int32_t *y, const float *W, float *G_out) {
+    if (!h) return CDGRAB_EINVAL;
+    if (N < 0 || in_dim < 1 || classes < 1 || classes > 1024 || in_dim > (1 << 20))
+        return fail(h, CDGRAB_EINVAL, "cdgrab_pergrad: bad sizes N=%lld in_dim=%lld classes=%lld",
+                    (long long)N, (long long)in_dim, (long long)classes);
+    if (N == 0) return CDGRAB_OK;
+    if (!X || !y || !W || !G_out) return fail(h, CDGRAB_EINVAL, "cdgrab_pergrad: null pointer");
+    size_t lds = (size_t)kGradWaves * (size_t)(in_dim + 1 + classes) * sizeof(float);
+    if (lds > 64 * 1024)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_pergrad: in_dim + classes too large for LDS staging");
+    HIP_TRY(h, hipSetDevice(h->device));
+    int64_t groups = (N + kGradWaves - 1) / kGradWaves;
+    hipLaunchKernelGGL(softmax_pergrad, dim3((unsigned)groups), dim3(kGradWaves * 64), lds, h->stream, X,
+                       y, W, G_out, N, (int)in_dim, (int)classes);
+    HIP_TRY(h, hipGetLastError());
+    return CDGRAB_OK;
+}
+
+int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *grads,
+                         cdgrab_gen_fn gen, void *gen_ctx, const int32_t *perm_in,
+                         int8_t *signs_out, int32_t *perm_out, float *r_out, double *r64_out,
+                         double *dots_out) {
+    if (!h) return CDGRAB_EINVAL;
+    if (m < 1 || n < 2 || (n & 1) || d < 1)
+        return fail(h, CDGRAB_EINVAL,
+                    "cdgrab_balance_epoch: need m>=1, even n>=2, d>=1 (got m=%lld n=%lld d=%lld)",
+                    (long long)m, (long long)n, (long long)d);
+    if ((grads == nullptr) == (gen == nullptr))
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: give exactly one of grads and gen");
+    if (!signs_out || !perm_out)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: signs_out and perm_out are required");
+    if (n > INT32_MAX) return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: n exceeds int32 range");
+    HIP_TRY(h, hipSetDevice(h->device));
+
+    const bool streamed = grads == nullptr;
+    cdgrab_plan plan;
+    int64_t align = 16;
+    if (!streamed) {
+        uintptr_t a = reinterpret_cast<uintptr_t>(grads);
+        align = (a % 16 == 0) ? 16 : (a % 8 == 0) ? 8 : 4;
+        if (a % 4) return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: grads is not 4-byte aligned");
+    }
+    int rc = plan_epoch(m, n, d, h->block_pairs_opt, streamed, align, h->num_cu, h->pass1_groups_opt, &plan);
+    if (rc != CDGRAB_OK) return fail(h, rc, "cdgrab_balance_epoch: sizes overflow or are invalid");
+    const int bb = plan.block_pairs;
+
+    // workspace
+    int64_t fixed_cap = 0;
+    rc = ensure(h, h->r_sum, h->r_cap, round_up(d, kTileE));
+    if (rc) return rc;
+    rc = ensure(h, h->partials, h->partials_cap, (int64_t)plan.pass1_groups * part_size(bb));
+    if (rc) return rc;
+    if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)PartLayout<32>::PART); if (rc) return rc; }
+    if (!h->eps_blk) { fixed_cap = 0; rc = ensure(h, h->eps_blk, fixed_cap, (int64_t)32); if (rc) return rc; }
+    if (streamed) { rc = ensure(h, h->staging, h->staging_cap, (int64_t)bb * 2 * d); if (rc) return rc; }
+
+    h->marks.clear();
+    h->events_used = 0;
+    h->have_timing = false;
+
+    hipLaunchKernelGGL(fill_zero_f64, dim3(std::min<int64_t>(4096, (h->r_cap + 255) / 256)), dim3(256), 0,
+                       h->stream, h->r_sum, h->r_cap);
+
+    RowMap rm;
+    rm.d = d; rm.m = m; rm.n = n;
+    rm.dense = streamed ? 0 : 1;
+    rm.base = streamed ? h->staging : grads;
+    for (int64_t blk = 0; blk < plan.blocks; ++blk) {
+        rm.p0 = blk * bb;
+        rm.nb = (int32_t)std::min<int64_t>(bb, plan.pairs - rm.p0);
+        if (streamed) {
+            MARK(h, 1, kGen);
+            int grc = gen(gen_ctx, rm.p0, rm.nb, h->staging, h->stream);
+            if (grc != 0)
+                return fail(h, CDGRAB_EGEN, "generator callback returned %d at pair %lld", grc,
+                            (long long)rm.p0);
+        }
+        MARK(h, 1, kBalance);
+        rc = (bb == 32) ? run_block_vw<32>(h, rm, plan, signs_out, dots_out)
+                        : run_block_vw<16>(h, rm, plan, signs_out, dots_out);
+        if (rc) return rc;
+    }
+    MARK(h, 1, kFinish);
+    {
+        int64_t work = m * (n / 2);
+        hipLaunchKernelGGL(build_pair_permutations, dim3((unsigned)((work + 255) / 256)), dim3(256), 0,
+                           h->stream, signs_out, perm_in, perm_out, m, n);
+        if (r_out || r64_out)
+            hipLaunchKernelGGL(export_running_sum, dim3((unsigned)std::min<int64_t>(8192, (d + 255) / 256)),
+                               dim3(256), 0, h->stream, h->r_sum, d, r_out, r64_out);
+    }
+    MARK(h, 1, -1);
+    HIP_TRY(h, hipGetLastError());
+    h->last = cdgrab_timing{};
+    h->last.blocks = plan.blocks;
+    h->last.block_pairs = bb;
+    h->last.pass1_groups = plan.pass1_groups;
+    h->have_timing = h->timing >= 1;
+    return CDGRAB_OK;
+}
+
+int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,
+                   const int32_t *perm_in, int32_t *perm_out) {
+    if (!h) return CDGRAB_EINVAL;
+    if (m < 1 || n < 1 || n > INT32_MAX || m > INT32_MAX)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_reorder: need m>=1, n>=1");
+    if (!signs || !perm_out) return fail(h, CDGRAB_EINVAL, "cdgrab_reorder: null pointer");
+    HIP_TRY(h, hipSetDevice(h->device));
+    if (!h->flag) { int64_t cap = 0; int rc = ensure(h, h->flag, cap, (int64_t)1); if (rc) return rc; }
+    HIP_TRY(h, hipMemsetAsync(h->flag, 0, sizeof(int32_t), h->stream));
+    hipLaunchKernelGGL(reorder_from_signs, dim3((unsigned)m), dim3(kScanThreads), 0, h->stream, signs,
+                       perm_in, perm_out, n, h->flag);
+    HIP_TRY(h, hipGetLastError());
+    int32_t bad = 0;
+    HIP_TRY(h, hipMemcpyAsync(&bad, h->flag, sizeof bad, hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    if (bad) return fail(h, CDGRAB_EINVAL, "cdgrab_reorder: a sign is neither +1 nor -1");
+    return CDGRAB_OK;
+}
+
+int cdgrab_get_timing(cdgrab_handle *h, cdgrab_timing *out) {
+    if (!h || !out) return CDGRAB_EINVAL;
+    if (!h->have_timing) return fail(h, CDGRAB_EINVAL, "cdgrab_get_timing: no timed epoch on this handle");
+    HIP_TRY(h, hipSetDevice(h->device));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    double sum[kIntervalKinds] = {0};
+    for (size_t q = 0; q + 1 < h->marks.size(); ++q) {
+        int kind = h->marks[q].kind_after;
+        if (kind < 0) continue;
+        float ms = 0.f;
+        HIP_TRY(h, hipEventElapsedTime(&ms, h->marks[q].ev, h->marks[q + 1].ev));
+        sum[kind] += ms;
+    }
+    cdgrab_timing t = h->last;
+    t.generator_ms = sum[kGen];
+    t.pass1_ms = sum[kPass1];
+    t.reduce_ms = sum[kReduce];
+    t.resolve_ms = sum[kResolve];
+    t.pass2_ms = sum[kPass2];
+    t.finish_ms = sum[kFinish];
+    // with per-kernel marks the balancer interval is split into its four kernels
+    t.balance_ms = sum[kBalance] + sum[kPass1] + sum[kReduce] + sum[kResolve] + sum[kPass2];
+    h->last = t;
+    *out = t;
+    return CDGRAB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,154 @@
+// Permutation builders and the per-example gradient kernel for gfx950.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cdgrab {
+
+// ---------------------------------------------------------------------------
+// Pair form of the reorder (one-step server algorithm, App. C.1): pair k of a
+// worker contributes exactly one row to the front list and one to the back list,
+// so the front pointer is k and the back pointer n-1-k -- no scan is needed.
+//   eps = +1: the second row (2k+1) carries +1 and goes to the front.
+__global__ void build_pair_permutations(const int8_t *__restrict__ signs, const int32_t *__restrict__ perm_in,
+                                        int32_t *__restrict__ perm_out, int64_t m, int64_t n)
+{
+    const int64_t half = n / 2;
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= m * half) return;
+    int64_t i = idx / half, k = idx - i * half;
+    int eps = signs[idx];
+    int64_t front = (eps == 1) ? 2 * k + 1 : 2 * k;
+    int64_t back = (eps == 1) ? 2 * k : 2 * k + 1;
+    const int32_t *pin = perm_in ? perm_in + i * n : nullptr;
+    int32_t *pout = perm_out + i * n;
+    pout[k] = pin ? pin[front] : (int32_t)front;
+    pout[n - 1 - k] = pin ? pin[back] : (int32_t)back;
+}
+
+// ---------------------------------------------------------------------------
+// General reorder from per-example signs (Sec. 2.1): a stable partition with the
+// negative part reversed.  One workgroup per worker walks the n signs in chunks;
+// an exclusive prefix count of +1 signs gives each positive its slot from the
+// front and each negative its slot from the back.
+constexpr int kScanThreads = 256;
+
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int up = __shfl_up(v, off, 64);
+        if (lane >= off) v += up;
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(kScanThreads) void reorder_from_signs(const int8_t *__restrict__ signs,
+                                                                   const int32_t *__restrict__ perm_in,
+                                                                   int32_t *__restrict__ perm_out, int64_t n,
+                                                                   int32_t *__restrict__ bad_flag)
+{
+    __shared__ int wave_tot[kScanThreads / 64];
+    const int64_t i = blockIdx.x;
+    const int8_t *sg = signs + i * n;
+    const int32_t *pin = perm_in ? perm_in + i * n : nullptr;
+    int32_t *pout = perm_out + i * n;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t pos_before = 0;  // +1 signs in earlier chunks
+    for (int64_t base = 0; base < n; base += kScanThreads) {
+        int64_t jpos = base + threadIdx.x;
+        int s = (jpos < n) ? (int)sg[jpos] : 0;
+        if (jpos < n && s != 1 && s != -1) atomicExch(bad_flag, 1);
+        int is_pos = (s == 1) ? 1 : 0;
+        int incl = wave_inclusive_scan(is_pos, lane);
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        int wave_off = 0, chunk_tot = 0;
+#pragma unroll
+        for (int w = 0; w < kScanThreads / 64; ++w) {
+            int tw = wave_tot[w];
+            if (w < wave) wave_off += tw;
+            chunk_tot += tw;
+        }
+        if (jpos < n) {
+            int64_t pos_rank = pos_before + wave_off + incl - is_pos;  // exclusive count of +1
+            int32_t id = pin ? pin[jpos] : (int32_t)jpos;
+            if (is_pos) pout[pos_rank] = id;
+            else pout[n - 1 - (jpos - pos_rank)] = id;                 // negatives fill from the back
+        }
+        pos_before += chunk_tot;
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Per-example gradient of softmax cross-entropy for a linear model ("CD-GraB
+// Workers", line 4).  One wavefront per example: the example's features are
+// staged in LDS, the logits are wave-reduced one class at a time, and the
+// (in_dim+1) x classes outer product is written with coalesced stores -- the
+// kernel is bound by that write (about ten times the bytes it reads).
+constexpr int kGradWaves = 4;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *__restrict__ X,
+                                                                   const int32_t *__restrict__ y,
+                                                                   const float *__restrict__ W,
+                                                                   float *__restrict__ G, int64_t N,
+                                                                   int in_dim, int classes)
+{
+    extern __shared__ float dyn[];  // per wave: in_dim + 1 features, then `classes` deltas
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int per_wave = in_dim + 1 + classes;
+    float *xs = dyn + wave * per_wave;
+    float *delta = xs + in_dim + 1;
+    const int64_t e = (int64_t)blockIdx.x * kGradWaves + wave;
+    const bool active = e < N;  // inactive waves still reach every barrier
+
+    if (active) {
+        const float *x = X + e * in_dim;
+        for (int r = lane; r < in_dim; r += 64) xs[r] = x[r];
+        if (lane == 0) xs[in_dim] = 1.0f;  // bias input
+    }
+    __syncthreads();
+
+    float mx = -INFINITY;
+    if (active) {
+        for (int c = 0; c < classes; ++c) {
+            float part = 0.f;
+            for (int r = lane; r <= in_dim; r += 64) part = fmaf(xs[r], W[(int64_t)r * classes + c], part);
+            float z = wave_sum(part);
+            if (lane == 0) delta[c] = z;
+            mx = fmaxf(mx, z);
+        }
+    }
+    __syncthreads();
+    float Z = 0.f;
+    if (active) {
+        for (int c = lane; c < classes; c += 64) Z += expf(delta[c] - mx);
+        Z = wave_sum(Z);
+    }
+    __syncthreads();
+    if (active) {
+        const int label = y[e];
+        for (int c = lane; c < classes; c += 64) {
+            float p = expf(delta[c] - mx) / Z;
+            delta[c] = p - (c == label ? 1.0f : 0.0f);
+        }
+    }
+    __syncthreads();
+    if (active) {
+        const int64_t dd = (int64_t)(in_dim + 1) * classes;
+        float *g = G + e * dd;
+        for (int64_t idx = lane; idx < dd; idx += 64) {
+            int r = (int)(idx / classes);
+            int c = (int)(idx - (int64_t)r * classes);
+            g[idx] = xs[r] * delta[c];
+        }
+    }
+}
+
+}  // namespace cdgrab

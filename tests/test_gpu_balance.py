@@ -1,0 +1,127 @@
+"""GPU parity tests of cdgrab_balance_epoch (dense input) against the CPU oracle.
+Every call goes through the C ABI via the ctypes binding."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from conftest import GOLDEN, load_hand_cases
+from parity import check_epoch
+
+pytestmark = pytest.mark.gpu
+
+HAND = load_hand_cases(os.path.join(GOLDEN, "hand_cases.txt"))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2302_00845_amd as p
+    return p
+
+
+def run_epoch(p, z, perm_in=None, block_pairs=0, pass1_groups=0):
+    m, n, d = z.shape
+    h = p.Handle(block_pairs=block_pairs, pass1_groups=pass1_groups)
+    zt = torch.from_numpy(z).cuda()
+    pt = torch.from_numpy(perm_in).cuda() if perm_in is not None else None
+    out = p.cdgrab_balance_epoch(h, m, n, d, grads=zt, perm_in=pt, want_r32=True, want_r64=True,
+                                 want_dots=True)
+    torch.cuda.synchronize()
+    got = {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
+    h.close()
+    return got
+
+
+@pytest.mark.parametrize("case", HAND, ids=[c["name"] for c in HAND])
+@pytest.mark.parametrize("bb", [16, 32])
+def test_hand_cases(lib, case, bb):
+    got = run_epoch(lib, case["rows"], block_pairs=bb)
+    assert got["signs"].tolist() == case["eps"].tolist()
+    assert got["r64"].tolist() == case["r"].tolist()
+    assert got["perm"].tolist() == case["perm"].tolist()
+
+
+@pytest.mark.parametrize("bb", [16, 32])
+@pytest.mark.parametrize("seed,m,n,d,maxabs", [
+    (0, 1, 2, 1, 3), (1, 1, 8, 3, 2), (2, 3, 6, 4, 2), (3, 4, 10, 7, 5), (4, 5, 4, 1, 1),
+    (5, 2, 16, 2, 1), (6, 7, 12, 33, 9), (7, 4, 64, 1024, 8), (8, 3, 50, 777, 4),
+    (9, 16, 8, 130, 2), (10, 33, 6, 258, 3), (11, 2, 70, 4100, 8),
+])
+def test_exact_integer_inputs_bitwise(lib, bb, seed, m, n, d, maxabs):
+    """Small-integer rows: all arithmetic is exact, so signs (ties included),
+    running sum and permutations must equal the oracle bit for bit.  Shapes cover
+    d < one tile, d not a multiple of 4 or 2, several tiles, ragged last block."""
+    z = workloads.integer_rows(seed, m, n, d, maxabs)
+    perm_in = workloads.random_perms(seed + 50, m, n)
+    got = run_epoch(lib, z, perm_in, block_pairs=bb)
+    rep = check_epoch(z, got, perm_in, expect_exact_signs=True)
+    assert rep["r64_rel_l2"] == 0.0
+    assert rep["dots_max_abs_err"] == 0.0
+
+
+@pytest.mark.parametrize("bb", [16, 32])
+def test_config1_tiny_epoch(lib, bb):
+    z = workloads.tiny_epoch(1234)                       # m=4, n=64, d=1024
+    got = run_epoch(lib, z, block_pairs=bb)
+    rep = check_epoch(z, got)
+    assert rep["in_margin_flips"] == 0 or not rep["free_run_equal"]
+
+
+@pytest.mark.parametrize("m,n,d", [(4, 64, 1024), (32, 16, 5000), (8, 40, 65536 + 12), (1, 256, 3000),
+                                   (3, 34, 7850)])
+def test_heavy_tailed_rows(lib, m, n, d):
+    z = workloads.heavy_rows(77, m, n, d)
+    got = run_epoch(lib, z)
+    check_epoch(z, got)
+
+
+def test_unaligned_base_pointer(lib):
+    """A gradient array that starts 4 bytes into an allocation takes the scalar-load path."""
+    m, n, d = 3, 10, 1001
+    z = workloads.integer_rows(21, m, n, d, 5)
+    buf = torch.zeros(m * n * d + 1, dtype=torch.float32, device="cuda")
+    view = buf[1:].view(m, n, d)
+    view.copy_(torch.from_numpy(z))
+    h = lib.Handle()
+    out = lib.cdgrab_balance_epoch(h, m, n, d, grads=view, want_r64=True, want_dots=True)
+    torch.cuda.synchronize()
+    got = {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
+    check_epoch(z, got, expect_exact_signs=True)
+
+
+def test_identical_rows_all_ties(lib):
+    m, n, d = 3, 8, 100
+    z = np.tile(np.arange(d, dtype=np.float32), (m, n, 1))
+    got = run_epoch(lib, z)
+    assert np.all(got["signs"] == 1)
+    assert np.all(got["r64"] == 0)
+    want = list(range(1, n, 2)) + list(range(n - 2, -1, -2))
+    for i in range(m):
+        assert got["perm"][i].tolist() == want
+
+
+def test_deterministic_and_group_count_invariant_on_exact_input(lib):
+    z = workloads.heavy_rows(5, 8, 32, 20000)
+    a = run_epoch(lib, z)
+    b = run_epoch(lib, z)
+    for k in ("signs", "perm", "r64", "dots"):
+        assert np.array_equal(a[k], b[k]), k                     # run-to-run bit identical
+    zi = workloads.integer_rows(6, 8, 32, 20000, 4)
+    c = run_epoch(lib, zi, pass1_groups=7)
+    e = run_epoch(lib, zi, pass1_groups=300)
+    for k in ("signs", "perm", "r64", "dots"):
+        assert np.array_equal(c[k], e[k]), k                     # exact input: grid does not matter
+
+
+def test_argument_errors(lib):
+    h = lib.Handle()
+    z = torch.zeros((2, 3, 4), dtype=torch.float32, device="cuda")
+    with pytest.raises(lib.CdgrabError) as ei:
+        lib.cdgrab_balance_epoch(h, 2, 3, 4, grads=z)            # odd n
+    assert ei.value.code == -1
+    with pytest.raises(lib.CdgrabError):
+        lib.cdgrab_balance_epoch(h, 2, 4, 4)                      # neither grads nor generator
+    with pytest.raises(lib.CdgrabError):
+        lib.Handle(block_pairs=24)

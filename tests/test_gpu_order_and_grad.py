@@ -1,0 +1,75 @@
+"""GPU parity tests of cdgrab_reorder and cdgrab_pergrad against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from parity import rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2302_00845_amd as p
+    return p
+
+
+@pytest.mark.parametrize("m,n", [(1, 1), (1, 2), (3, 7), (4, 256), (5, 257), (2, 1000), (16, 3750), (1, 48816)])
+@pytest.mark.parametrize("with_perm", [False, True])
+def test_reorder_matches_oracle(lib, m, n, with_perm):
+    signs = workloads.random_signs(m * 1000 + n, m, n)
+    perm_in = workloads.random_perms(n, m, n) if with_perm else None
+    h = lib.Handle()
+    out = lib.cdgrab_reorder(h, torch.from_numpy(signs).cuda(),
+                             torch.from_numpy(perm_in).cuda() if with_perm else None).cpu().numpy()
+    for i in range(m):
+        want = oracle.reorder(signs[i], perm_in[i] if with_perm else None)
+        assert np.array_equal(out[i], want)
+
+
+def test_reorder_all_one_sign(lib):
+    h = lib.Handle()
+    n = 300
+    for s in (1, -1):
+        signs = np.full((2, n), s, np.int8)
+        out = lib.cdgrab_reorder(h, torch.from_numpy(signs).cuda()).cpu().numpy()
+        want = np.arange(n) if s == 1 else np.arange(n)[::-1]
+        assert np.array_equal(out[0], want) and np.array_equal(out[1], want)
+
+
+def test_reorder_rejects_bad_sign(lib):
+    h = lib.Handle()
+    signs = np.ones((2, 10), np.int8)
+    signs[1, 3] = 0
+    with pytest.raises(lib.CdgrabError) as ei:
+        lib.cdgrab_reorder(h, torch.from_numpy(signs).cuda())
+    assert ei.value.code == -1
+
+
+@pytest.mark.parametrize("N,in_dim,classes", [(1, 1, 1), (5, 7, 4), (64, 784, 10), (257, 784, 10), (33, 100, 70)])
+def test_pergrad_matches_oracle(lib, N, in_dim, classes):
+    X, y, W = workloads.softmax_problem(N, N, in_dim, classes)
+    if classes > 1:
+        W = (W * 20).astype(np.float32)
+    h = lib.Handle()
+    G = lib.cdgrab_pergrad(h, torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(),
+                           torch.from_numpy(W).cuda()).cpu().numpy()
+    want = oracle.softmax_pergrad(X, y, W)
+    if classes == 1:
+        assert np.all(np.abs(G) <= 1e-6)                  # softmax of one class: delta = 0
+        return
+    for e in range(N):
+        assert rel_l2(G[e], want[e]) <= 1e-5
+    assert rel_l2(G, want) <= 1e-5
+
+
+def test_pergrad_empty_and_errors(lib):
+    h = lib.Handle()
+    X = torch.zeros((0, 5), dtype=torch.float32, device="cuda")
+    y = torch.zeros((0,), dtype=torch.int32, device="cuda")
+    W = torch.zeros((6, 3), dtype=torch.float32, device="cuda")
+    assert lib.cdgrab_pergrad(h, X, y, W).shape == (0, 18)
+    with pytest.raises(TypeError):
+        lib.cdgrab_pergrad(h, X.double(), y, W)
