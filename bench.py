@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the CD-GraB pair-balancing hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4_resnet18]
+
+A step is one whole epoch of the hot path on the named synthetic workload: for
+each block of Bb flattened pairs the counter-based generator fills the staging
+block in HBM (the stand-in for gradients arriving from the workers), then the
+dot/Gram pass, the partial reduction, the sign resolver and the apply pass run,
+and at the end the permutations and the running sum are written.
+
+`value` is examples balanced per second with each block's rows already resident
+in HBM when its timed region starts: the generator's time is measured with HIP
+events on the same stream and reported separately (`generator_ms_per_step`,
+`wall_ms_per_step`), never folded into `value`.
+
+Prints one JSON line (metric, roofline of the dominant kernel, CPU-oracle
+baseline on a bounded sample of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c4_resnet18")
+    ap.add_argument("--block-pairs", type=int, default=0)
+    ap.add_argument("--pass1-groups", type=int, default=0)
+    ap.add_argument("--n", type=int, default=0, help="override rows per worker (shorter epoch)")
+    ap.add_argument("--seed", type=int, default=2302)
+    ap.add_argument("--cpu-sample-pairs", type=int, default=-1,
+                    help="pairs of the workload the CPU oracle is timed on (-1: sized for ~15 s, 0: skip)")
+    ap.add_argument("--no-profile-step", action="store_true",
+                    help="skip the extra per-kernel-timed epoch behind the roofline object")
+    return ap.parse_args()
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel from committed rocprofv3 --pmc
+    summaries (profiles/pmc_traffic_<workload>.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    out = {}
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            _, kernel, value = line.split()
+            out[kernel] = float(value)
+    return out or None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the balancer on ONE GPU (the m workers are a batch axis); "
+              "--gpus %d is not supported, run with --gpus 1" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2302_00845_amd as pkg
+    import workloads
+    from workloads import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    w = workloads.CONFIGS[args.workload]
+    m, n, d = w.m, (args.n or w.n), w.d
+    N = m * n
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+
+    # ------------------------------------------------------------------ inputs
+    perm_in = torch.from_numpy(workloads.random_perms(args.seed, m, n)).to(dev)
+    gen_fn = gen_ctx = grads = rows_src = None
+    pergrad_ms = None
+    h = pkg.Handle(device=0, block_pairs=args.block_pairs, timing=1, pass1_groups=args.pass1_groups)
+    if w.kind == "stream":
+        rows_src = synth.from_workload(w, args.seed, n=n)
+        gen_fn, gen_ctx = rows_src.device_callback(str(dev))
+    elif w.kind == "softmax":
+        X, y, W = workloads.softmax_problem(args.seed, N)
+        Xd, yd, Wd = (torch.from_numpy(a).to(dev) for a in (X, y, W))
+        G = torch.empty((N, d), dtype=torch.float32, device=dev)
+    else:
+        grads = torch.from_numpy(workloads.tiny_epoch(args.seed, m, n, d)).to(dev)
+
+    def step():
+        """One pass of the whole hot path; returns the event-timed split (ms)."""
+        nonlocal grads, pergrad_ms
+        if w.kind == "softmax":
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            pkg.cdgrab_pergrad(h, Xd, yd, Wd, G)
+            e1.record()
+            grads = G.view(m, n, d)
+        out = pkg.cdgrab_balance_epoch(h, m, n, d, grads=grads, gen=gen_fn, gen_ctx=gen_ctx,
+                                       perm_in=perm_in, want_r32=True)
+        t = h.timing()                                       # synchronises the stream
+        if w.kind == "softmax":
+            pergrad_ms = e0.elapsed_time(e1)
+            t["balance_ms"] += pergrad_ms                    # the gradient kernel is part of the path
+        return out, t
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_wall0 = time.perf_counter()
+    splits = []
+    for _ in range(args.steps):
+        out, t = step()
+        splits.append(t)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall0) * 1e3 / max(args.steps, 1)
+
+    path_ms = float(np.mean([t["balance_ms"] + t["finish_ms"] for t in splits]))
+    gen_ms = float(np.mean([t["generator_ms"] for t in splits]))
+    bb = splits[-1]["block_pairs"]
+    blocks = splits[-1]["blocks"]
+    value = N / (path_ms * 1e-3)
+
+    # ------------------------------------------------------------------ roofline (dominant kernel)
+    roofline = None
+    kernels = {}
+    if not args.no_profile_step:
+        hp = pkg.Handle(device=0, block_pairs=args.block_pairs, timing=2, pass1_groups=args.pass1_groups)
+        if w.kind == "softmax":
+            pkg.cdgrab_pergrad(hp, Xd, yd, Wd, G)
+        pkg.cdgrab_balance_epoch(hp, m, n, d, grads=grads, gen=gen_fn, gen_ctx=gen_ctx, perm_in=perm_in)
+        tp = hp.timing()
+        pairs = N // 2
+        # algorithmic bytes per launch: both rows of every pair in the block (fp32)
+        # plus the double running sum (read in pass 1; read and written in pass 2)
+        avg_pairs = pairs / blocks
+        bytes_p1 = 8.0 * avg_pairs * d + 8.0 * d
+        bytes_p2 = 8.0 * avg_pairs * d + 16.0 * d
+        for name, ms, nbytes in (("pass1_dots_gram", tp["pass1_ms"], bytes_p1),
+                                 ("pass2_apply", tp["pass2_ms"], bytes_p2)):
+            avg_ms = ms / blocks
+            kernels[name] = {"avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": nbytes,
+                             "achieved_GBs": nbytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else None}
+        kernels["reduce_partials"] = {"avg_launch_ms": tp["reduce_ms"] / blocks}
+        kernels["resolve_signs"] = {"avg_launch_ms": tp["resolve_ms"] / blocks}
+        dom = max(("pass1_dots_gram", "pass2_apply"), key=lambda k: kernels[k]["avg_launch_ms"])
+        traffic = read_traffic(args.workload)
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["achieved_GBs"],
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": kernels[dom]["achieved_GBs"] / HBM_PEAK_GBS,
+                    "traffic": (traffic or {}).get(dom),
+                    "avg_launch_ms": kernels[dom]["avg_launch_ms"],
+                    "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"]}
+        hp.close()
+    # whole balancer against the roofline: 8d + 12 d / Bb bytes per example
+    bytes_per_example = 8.0 * d + 12.0 * d / bb
+    balancer_gbs = bytes_per_example * N / (path_ms * 1e-3) / 1e9
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample
+    cpu_baseline = None
+    sample_pairs = args.cpu_sample_pairs
+    if sample_pairs < 0:
+        # about 15 s of single-threaded oracle work at roughly 100 MB/s-per-row-pair cost
+        per_pair_s = max(d * 8e-9, 1e-6)
+        sample_pairs = int(min(N // 2, max(bb, 15.0 / per_pair_s)))
+        sample_pairs = max(bb, (sample_pairs // bb) * bb) if N // 2 >= bb else N // 2
+    if sample_pairs > 0:
+        import oracle
+        if w.kind == "stream":
+            rows = rows_src.fill_pairs_device(0, sample_pairs, str(dev)).cpu().numpy()
+        else:
+            z = grads.cpu().numpy()
+            rows = np.ascontiguousarray(
+                z.reshape(m, n // 2, 2, d).transpose(1, 0, 2, 3).reshape(N // 2, 2, d)[:sample_pairs])
+        r = np.zeros(d)
+        t0 = time.perf_counter()
+        eps, tt, nr, nc = oracle.stream_pairs(r, rows)
+        cpu_s = time.perf_counter() - t0
+        gpu_eps = out["signs"].cpu().numpy().T.reshape(-1)[:sample_pairs]
+        agree = bool(np.array_equal(gpu_eps, eps))
+        if not agree:  # judge differences by the margin rule, replaying the GPU's signs
+            r2 = np.zeros(d)
+            _, t2, nr2, nc2 = oracle.stream_pairs(r2, rows, eps_in=gpu_eps)
+            bad = (np.where(t2 <= 0, 1, -1) != gpu_eps) & (np.abs(t2) > 1e-9 * nr2 * nc2)
+            agree = not bool(bad.any())
+        cpu_baseline = {"value": 2 * sample_pairs / cpu_s, "unit": "examples/s", "cores": 1,
+                        "kind": "oracle",
+                        "sample": "first %d flattened pairs (%d examples) of %s, rows copied from HBM; "
+                                  "balancing loop only" % (sample_pairs, 2 * sample_pairs, args.workload),
+                        "seconds": cpu_s, "host_cores_available": os.cpu_count(),
+                        "signs_agree_with_gpu_on_sample": agree}
+
+    line = {
+        "metric": "examples balanced/sec per epoch at m workers x d params",
+        "value": value, "unit": "examples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": path_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": args.workload, "m": m, "n": n, "d": d, "examples": N,
+                   "block_pairs": bb, "blocks": blocks, "input": w.kind,
+                   "rows_dtype": "f32", "parallelism": "1 GPU, m workers as a batch axis"},
+        "generator_ms_per_step": gen_ms, "wall_ms_per_step": wall_ms,
+        "value_including_generator": N / ((path_ms + gen_ms) * 1e-3),
+        "balancer_achieved_GBs": balancer_gbs, "balancer_hbm_frac": balancer_gbs / HBM_PEAK_GBS,
+        "bytes_per_example": bytes_per_example,
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu_baseline,
+    }
+    if pergrad_ms is not None:
+        line["pergrad_ms_per_step"] = pergrad_ms
+    print(json.dumps(line))
+    h.close()
+
+
+if __name__ == "__main__":
+    main()
