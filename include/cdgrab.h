@@ -65,6 +65,8 @@ typedef struct cdgrab_plan {
     int64_t blocks;          /* ceil(pairs / block_pairs)                             */
     int32_t block_pairs;     /* Bb                                                    */
     int32_t vector_width;    /* fp32 elements per global load: 4, 2 or 1              */
+    int32_t tile_elems;      /* elements of d per LDS tile of the dot/Gram pass        */
+    int32_t reserved;
     int32_t pass1_groups;    /* workgroups of the dot/Gram pass                       */
     int32_t pass2_groups;    /* workgroups of the apply pass                          */
     int64_t workspace_bytes; /* running sum + partials (+ staging when streaming)     */

@@ -48,6 +48,7 @@ class Timing(ctypes.Structure):
 class Plan(ctypes.Structure):
     _fields_ = [("pairs", ctypes.c_int64), ("blocks", ctypes.c_int64),
                 ("block_pairs", ctypes.c_int32), ("vector_width", ctypes.c_int32),
+                ("tile_elems", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("pass1_groups", ctypes.c_int32), ("pass2_groups", ctypes.c_int32),
                 ("workspace_bytes", ctypes.c_int64), ("staging_bytes", ctypes.c_int64),
                 ("bytes_per_example", ctypes.c_double)]

@@ -22,50 +22,58 @@ namespace cdgrab {
 
 constexpr int kThreads = 256;       // workgroup size of the streaming kernels
 constexpr int kWaves = kThreads / 64;
-constexpr int kTileE = 64;          // elements of d per LDS tile
-constexpr int kLdsStride = kTileE + 4;  // floats per LDS row (16 B aligned, bank-skewed)
+constexpr int kPadE = 128;          // the running sum is padded to a multiple of this many elements
 
 typedef double double4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
 
 // Where the rows of the current block live.  Flattened pair p = p0 + j belongs to
-// worker p % m and is that worker's pair p / m.  Dense input is [m][n][d]; a
-// staging block is [Bb][2][d].
+// worker p % m and is that worker's pair p / m; the host passes p0 already split as
+// (k0, i0) = (p0 / m, p0 % m).  Dense input is [m][n][d]; a staging block is [Bb][2][d].
 struct RowMap {
     const float *base;
     int64_t d;
-    int64_t p0;
-    int64_t m;
     int64_t n;
+    int64_t k0;     // pair index (per worker) of the block's first flattened pair
+    int32_t i0;     // worker of the block's first flattened pair
+    int32_t m;
     int32_t dense;  // 1: base is the caller's [m][n][d] array; 0: base is a staging block
     int32_t nb;     // valid pairs in this block (<= Bb)
 
     __device__ __forceinline__ const float *row(int j, int which) const {
         if (dense) {
-            int64_t p = p0 + j;
-            int64_t k = p / m;
-            int64_t i = p - k * m;
-            return base + ((i * n) + 2 * k + which) * d;
+            uint32_t q = (uint32_t)(i0 + j);
+            uint32_t dk = q / (uint32_t)m;
+            uint32_t i = q - dk * (uint32_t)m;
+            return base + (((int64_t)i * n) + 2 * (k0 + dk) + which) * d;
         }
         return base + (int64_t)(2 * j + which) * d;
     }
 };
 
-// Four consecutive fp32 elements starting at element e of a row, zero beyond d.
-// VW is the widest load the row alignment allows (4, 2 or 1 floats).
+// Four consecutive fp32 elements starting at element e of a row, zero beyond d or
+// for a missing row.  VW is the widest load the row alignment allows (4, 2 or 1
+// floats).  Rows are read exactly once per pass, so the loads carry the
+// non-temporal hint: the streamed rows then do not evict the running sum, which
+// is re-read and rewritten every block, from the last-level cache.
 template <int VW>
 __device__ __forceinline__ float4 load4(const float *row, int64_t e, int64_t d) {
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (row == nullptr) return v;
     if constexpr (VW == 4) {
-        if (e < d) v = *reinterpret_cast<const float4 *>(row + e);
+        if (e < d) {
+            float4_t t = __builtin_nontemporal_load(reinterpret_cast<const float4_t *>(row + e));
+            v = make_float4(t.x, t.y, t.z, t.w);
+        }
     } else if constexpr (VW == 2) {
-        if (e < d) { float2 t = *reinterpret_cast<const float2 *>(row + e); v.x = t.x; v.y = t.y; }
-        if (e + 2 < d) { float2 t = *reinterpret_cast<const float2 *>(row + e + 2); v.z = t.x; v.w = t.y; }
+        if (e < d) { float2_t t = __builtin_nontemporal_load(reinterpret_cast<const float2_t *>(row + e)); v.x = t.x; v.y = t.y; }
+        if (e + 2 < d) { float2_t t = __builtin_nontemporal_load(reinterpret_cast<const float2_t *>(row + e + 2)); v.z = t.x; v.w = t.y; }
     } else {
-        if (e < d) v.x = row[e];
-        if (e + 1 < d) v.y = row[e + 1];
-        if (e + 2 < d) v.z = row[e + 2];
-        if (e + 3 < d) v.w = row[e + 3];
+        if (e < d) v.x = __builtin_nontemporal_load(row + e);
+        if (e + 1 < d) v.y = __builtin_nontemporal_load(row + e + 1);
+        if (e + 2 < d) v.z = __builtin_nontemporal_load(row + e + 2);
+        if (e + 3 < d) v.w = __builtin_nontemporal_load(row + e + 3);
     }
     return v;
 }
@@ -89,22 +97,29 @@ __device__ __forceinline__ void mfma_f64_16x16_coord(int lane, int v, int &i, in
 
 // ---------------------------------------------------------------------------
 // Pass 1: partial dots <r, d_k> and partial Gram <d_j, d_k> over a strided set
-// of 64-element tiles of d.  One workgroup = 4 waves; each tile is staged
-// through LDS (coalesced 16 B global loads -> row-per-lane MFMA operands).
+// of TE-element tiles of d.  One workgroup = 4 waves; each tile is staged
+// through LDS (coalesced 16 B global loads -> row-per-lane MFMA operands), with
+// the next tile's loads in flight while the current one is consumed.
 // Lane (row = lane % 16, kslot = lane / 16) of wave w owns elements
-// 16 w + 4 kslot .. +3 of the tile for pair `row` of each 16-pair group.
-template <int BB, int VW>
+// (TE/4) w + 16 s + 4 kslot .. +3 (s = 0 .. TE/64-1) of the tile for pair `row`
+// of each 16-pair group.  TE = 128 halves the barriers per byte and is the
+// streaming configuration; TE = 64 gives short rows more workgroups.
+template <int BB, int VW, int TE>
 __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const double *__restrict__ r_sum,
                                                             double *__restrict__ partials,
                                                             int64_t ntiles)
 {
     using L = PartLayout<BB>;
     constexpr int RG = L::RG;
-    constexpr int LOADS = 2 * BB / 16;  // 16 B loads per thread per tile
-    constexpr int TILE_FLOATS = BB * kLdsStride;
+    constexpr int TPR = TE / 4;               // threads covering one row of the tile
+    constexpr int RPI = kThreads / TPR;       // rows covered by one load instruction
+    constexpr int LOADS = 2 * BB / RPI;       // 16 B loads per thread per tile
+    constexpr int STRIDE = TE + 4;            // floats per LDS row (16 B aligned, bank-skewed)
+    constexpr int TILE_FLOATS = BB * STRIDE;
+    constexpr int EPW = TE / kWaves;          // elements per wave per tile
     // LDS: two stages of (first rows, second rows, running-sum chunk); the final
     // cross-wave reduction reuses the same bytes.
-    constexpr int STAGE_BYTES = 2 * TILE_FLOATS * 4 + kTileE * 8;
+    constexpr int STAGE_BYTES = 2 * TILE_FLOATS * 4 + TE * 8;
     constexpr int RED_BYTES = kWaves * (L::GRAM + RG * 64) * 8;
     constexpr int SMEM = (2 * STAGE_BYTES > RED_BYTES) ? 2 * STAGE_BYTES : RED_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
@@ -114,17 +129,16 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
     const int wave = tid >> 6;
     const int64_t d = rm.d;
 
-    // global -> register mapping: 16 threads cover one row's 64 elements
-    const int lrow = tid >> 4;
-    const int chunk = tid & 15;
+    const int lrow = tid / TPR;
+    const int chunk = tid % TPR;
     const float *src[LOADS];
     int lds_off[LOADS];
 #pragma unroll
     for (int u = 0; u < LOADS; ++u) {
-        int rr = u * 16 + lrow;        // 0 .. 2*BB-1
+        int rr = u * RPI + lrow;       // 0 .. 2*BB-1
         int j = rr >> 1, which = rr & 1;
         src[u] = (j < rm.nb) ? rm.row(j, which) : nullptr;
-        lds_off[u] = (which * TILE_FLOATS + j * kLdsStride + chunk * 4) * 4;
+        lds_off[u] = (which * TILE_FLOATS + j * STRIDE + chunk * 4) * 4;
     }
 
     double4_t acc[L::NT];
@@ -136,7 +150,6 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
 
     const int mrow = lane & 15;
     const int kslot = lane >> 4;
-    const int eo = 16 * wave + 4 * kslot;  // element offset inside the tile
 
     float4 stage_regs[LOADS];
     double2 stage_s = make_double2(0.0, 0.0);
@@ -144,8 +157,8 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
     int64_t tile = blockIdx.x;
     if (tile < ntiles) {
 #pragma unroll
-        for (int u = 0; u < LOADS; ++u) stage_regs[u] = load4<VW>(src[u], tile * kTileE + chunk * 4, d);
-        if (tid < kTileE / 2) stage_s = *reinterpret_cast<const double2 *>(r_sum + tile * kTileE + tid * 2);
+        for (int u = 0; u < LOADS; ++u) stage_regs[u] = load4<VW>(src[u], tile * TE + chunk * 4, d);
+        if (tid < TE / 2) stage_s = *reinterpret_cast<const double2 *>(r_sum + tile * TE + tid * 2);
     }
     int buf = 0;
     for (; tile < ntiles; tile += gridDim.x) {
@@ -153,7 +166,7 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
 #pragma unroll
         for (int u = 0; u < LOADS; ++u)
             *reinterpret_cast<float4 *>(stage + lds_off[u]) = stage_regs[u];
-        if (tid < kTileE / 2)
+        if (tid < TE / 2)
             *reinterpret_cast<double2 *>(stage + 2 * TILE_FLOATS * 4 + tid * 16) = stage_s;
         __syncthreads();
 
@@ -161,41 +174,45 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
         int64_t nxt = tile + gridDim.x;
         if (nxt < ntiles) {
 #pragma unroll
-            for (int u = 0; u < LOADS; ++u) stage_regs[u] = load4<VW>(src[u], nxt * kTileE + chunk * 4, d);
-            if (tid < kTileE / 2) stage_s = *reinterpret_cast<const double2 *>(r_sum + nxt * kTileE + tid * 2);
+            for (int u = 0; u < LOADS; ++u) stage_regs[u] = load4<VW>(src[u], nxt * TE + chunk * 4, d);
+            if (tid < TE / 2) stage_s = *reinterpret_cast<const double2 *>(r_sum + nxt * TE + tid * 2);
         }
 
         const float *first = reinterpret_cast<const float *>(stage);
         const float *second = first + TILE_FLOATS;
         const double *sv = reinterpret_cast<const double *>(stage + 2 * TILE_FLOATS * 4);
-        float4 a[RG], b[RG];
 #pragma unroll
-        for (int g = 0; g < RG; ++g) {
-            a[g] = *reinterpret_cast<const float4 *>(first + (16 * g + mrow) * kLdsStride + eo);
-            b[g] = *reinterpret_cast<const float4 *>(second + (16 * g + mrow) * kLdsStride + eo);
-        }
-        double2 s01 = *reinterpret_cast<const double2 *>(sv + eo);
-        double2 s23 = *reinterpret_cast<const double2 *>(sv + eo + 2);
-        const double se[4] = {s01.x, s01.y, s23.x, s23.y};
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            double dd[RG];
+        for (int ks = 0; ks < EPW / 16; ++ks) {
+            const int eo = EPW * wave + 16 * ks + 4 * kslot;  // element offset inside the tile
+            float4 a[RG], b[RG];
 #pragma unroll
             for (int g = 0; g < RG; ++g) {
-                float fa = (t == 0) ? a[g].x : (t == 1) ? a[g].y : (t == 2) ? a[g].z : a[g].w;
-                float fb = (t == 0) ? b[g].x : (t == 1) ? b[g].y : (t == 2) ? b[g].z : b[g].w;
-                dd[g] = (double)fb - (double)fa;
-                pdot[g] = __builtin_fma(se[t], dd[g], pdot[g]);
+                a[g] = *reinterpret_cast<const float4 *>(first + (16 * g + mrow) * STRIDE + eo);
+                b[g] = *reinterpret_cast<const float4 *>(second + (16 * g + mrow) * STRIDE + eo);
             }
-            // upper-triangular tiles, row group g (A operand) x row group h >= g (B operand)
-            int q = 0;
+            double2 s01 = *reinterpret_cast<const double2 *>(sv + eo);
+            double2 s23 = *reinterpret_cast<const double2 *>(sv + eo + 2);
+            const double se[4] = {s01.x, s01.y, s23.x, s23.y};
 #pragma unroll
-            for (int g = 0; g < RG; ++g)
+            for (int t = 0; t < 4; ++t) {
+                double dd[RG];
 #pragma unroll
-                for (int h = g; h < RG; ++h) {
-                    acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(dd[g], dd[h], acc[q], 0, 0, 0);
-                    ++q;
+                for (int g = 0; g < RG; ++g) {
+                    float fa = (t == 0) ? a[g].x : (t == 1) ? a[g].y : (t == 2) ? a[g].z : a[g].w;
+                    float fb = (t == 0) ? b[g].x : (t == 1) ? b[g].y : (t == 2) ? b[g].z : b[g].w;
+                    dd[g] = (double)fb - (double)fa;
+                    pdot[g] = __builtin_fma(se[t], dd[g], pdot[g]);
                 }
+                // upper-triangular tiles, row group g (A operand) x row group h >= g (B operand)
+                int q = 0;
+#pragma unroll
+                for (int g = 0; g < RG; ++g)
+#pragma unroll
+                    for (int h = g; h < RG; ++h) {
+                        acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(dd[g], dd[h], acc[q], 0, 0, 0);
+                        ++q;
+                    }
+            }
         }
         buf ^= 1;
     }
@@ -230,53 +247,63 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
 }
 
 // ---------------------------------------------------------------------------
-// Fixed-order reduction of the per-workgroup partials: 32 entries per workgroup,
-// 8 segments of the partial list per entry, segments combined in order.
+// Fixed-order reduction of the per-workgroup partials, first level: the list of
+// workgroups is cut into kReduceSlices slices (blockIdx.y); each workgroup sums
+// its slice for 32 consecutive entries, 8 sub-ranges per entry combined in order.
+// The resolver adds the kReduceSlices slice sums, again in order.
 constexpr int kReduceEntries = 32;
-constexpr int kReduceSegs = kThreads / kReduceEntries;
+constexpr int kReduceSubs = kThreads / kReduceEntries;
+constexpr int kReduceSlices = 8;
 
 __global__ __launch_bounds__(kThreads) void reduce_partials(const double *__restrict__ partials,
-                                                            double *__restrict__ reduced, int part,
+                                                            double *__restrict__ sliced, int part,
                                                             int groups)
 {
-    __shared__ double segsum[kReduceSegs][kReduceEntries];
+    __shared__ double subsum[kReduceSubs][kReduceEntries];
     const int ent = threadIdx.x % kReduceEntries;
-    const int seg = threadIdx.x / kReduceEntries;
+    const int sub = threadIdx.x / kReduceEntries;
     const int entry = blockIdx.x * kReduceEntries + ent;
-    const int g0 = (int)((int64_t)seg * groups / kReduceSegs);
-    const int g1 = (int)((int64_t)(seg + 1) * groups / kReduceSegs);
+    const int slice = blockIdx.y;
+    const int s0 = (int)((int64_t)slice * groups / kReduceSlices);
+    const int s1 = (int)((int64_t)(slice + 1) * groups / kReduceSlices);
+    const int g0 = s0 + (int)((int64_t)sub * (s1 - s0) / kReduceSubs);
+    const int g1 = s0 + (int)((int64_t)(sub + 1) * (s1 - s0) / kReduceSubs);
     double sum = 0.0;
     if (entry < part)
         for (int g = g0; g < g1; ++g) sum += partials[(int64_t)g * part + entry];
-    segsum[seg][ent] = sum;
+    subsum[sub][ent] = sum;
     __syncthreads();
-    if (seg == 0 && entry < part) {
+    if (sub == 0 && entry < part) {
         double tot = 0.0;
 #pragma unroll
-        for (int q = 0; q < kReduceSegs; ++q) tot += segsum[q][ent];
-        reduced[entry] = tot;
+        for (int q = 0; q < kReduceSubs; ++q) tot += subsum[q][ent];
+        sliced[(int64_t)slice * part + entry] = tot;
     }
 }
 
 // ---------------------------------------------------------------------------
-// Sequential sign resolution by one wavefront.  Lane k carries
+// Sequential sign resolution.  All 256 threads finish the reduction and unpack
+// the Gram tiles into LDS; then one wavefront walks the block: lane k carries
 // t_k = <r, d_k> + sum_{j<k, decided} eps_j G[j][k]; step j broadcasts t_j,
 // fixes eps_j = +1 if t_j <= 0 else -1 and updates the later lanes.
 template <int BB>
-__global__ __launch_bounds__(64) void resolve_signs(const double *__restrict__ reduced, int nb,
-                                                    int64_t p0, int64_t m, int64_t half_n,
-                                                    int8_t *__restrict__ eps_blk,
-                                                    int8_t *__restrict__ signs_out,
-                                                    double *__restrict__ dots_out)
+__global__ __launch_bounds__(kThreads) void resolve_signs(const double *__restrict__ sliced, int nb,
+                                                          int64_t k0, int32_t i0, int32_t m, int64_t half_n,
+                                                          int8_t *__restrict__ eps_blk,
+                                                          int8_t *__restrict__ signs_out,
+                                                          double *__restrict__ dots_out)
 {
     using L = PartLayout<BB>;
     __shared__ double G[BB][BB + 1];
-    const int lane = threadIdx.x;
-    for (int idx = lane; idx < L::GRAM; idx += 64) {
+    __shared__ double P[BB];
+    for (int idx = threadIdx.x; idx < L::PART; idx += kThreads) {
+        double val = 0.0;
+#pragma unroll
+        for (int s = 0; s < kReduceSlices; ++s) val += sliced[(int64_t)s * L::PART + idx];
+        if (idx >= L::GRAM) { P[idx - L::GRAM] = val; continue; }
         int tile = idx >> 8, v = (idx >> 6) & 3, ln = idx & 63;
         int i, j;
         mfma_f64_16x16_coord(ln, v, i, j);
-        double val = reduced[idx];
         if (L::RG == 1) {
             G[i][j] = val;
         } else {
@@ -287,13 +314,16 @@ __global__ __launch_bounds__(64) void resolve_signs(const double *__restrict__ r
         }
     }
     __syncthreads();
-    double t = (lane < nb) ? reduced[L::GRAM + lane] : 0.0;
+    if (threadIdx.x >= 64) return;
+    const int lane = threadIdx.x;
+    double t = (lane < nb) ? P[lane] : 0.0;
     for (int j = 0; j < nb; ++j) {
         double tj = __shfl(t, j, 64);
         int eps = (tj <= 0.0) ? 1 : -1;
         if (lane == j) {
-            int64_t p = p0 + j;
-            int64_t k = p / m, i = p - k * m;
+            uint32_t q = (uint32_t)(i0 + j);
+            uint32_t dk = q / (uint32_t)m;
+            int64_t i = q - dk * (uint32_t)m, k = k0 + dk;
             eps_blk[j] = (int8_t)eps;
             signs_out[i * half_n + k] = (int8_t)eps;
             if (dots_out) dots_out[i * half_n + k] = tj;
@@ -304,8 +334,9 @@ __global__ __launch_bounds__(64) void resolve_signs(const double *__restrict__ r
 
 // ---------------------------------------------------------------------------
 // Pass 2: r += sum_k eps_k d_k.  Each thread owns four consecutive elements and
-// streams the block's rows through registers.
-template <int BB, int VW>
+// streams the block's rows through registers.  FULL = the block holds all BB
+// pairs (no per-pair test inside the unrolled loop).
+template <int BB, int VW, bool FULL>
 __global__ __launch_bounds__(kThreads) void pass2_apply(RowMap rm, const int8_t *__restrict__ eps_blk,
                                                         double *__restrict__ r_sum)
 {
@@ -315,7 +346,7 @@ __global__ __launch_bounds__(kThreads) void pass2_apply(RowMap rm, const int8_t 
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll 8
     for (int j = 0; j < BB; ++j) {
-        if (j < rm.nb) {
+        if (FULL || j < rm.nb) {
             float4 a = load4<VW>(rm.row(j, 0), e, d);
             float4 b = load4<VW>(rm.row(j, 1), e, d);
             double sg = (double)eps_blk[j];

@@ -42,7 +42,7 @@ struct cdgrab_handle {
 
     double *r_sum = nullptr;   int64_t r_cap = 0;         // doubles
     double *partials = nullptr; int64_t partials_cap = 0; // doubles
-    double *reduced = nullptr;                            // PartLayout<32>::PART doubles
+    double *reduced = nullptr;                            // kReduceSlices x PartLayout<32>::PART doubles
     int8_t *eps_blk = nullptr;                            // 32 signs
     int32_t *flag = nullptr;                              // reorder's bad-sign flag
     float *staging = nullptr;  int64_t staging_cap = 0;   // floats
@@ -93,17 +93,21 @@ int plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs, int32_t str
     if (m < 1 || n < 2 || (n & 1) || d < 1 || !plan) return CDGRAB_EINVAL;
     if (block_pairs != 0 && block_pairs != 16 && block_pairs != 32) return CDGRAB_EINVAL;
     if (base_align < 4 || (base_align & (base_align - 1))) return CDGRAB_EINVAL;
-    if (m > (INT64_MAX / n) / d) return CDGRAB_EINVAL;
+    if (m > (INT64_MAX / n) / d || m > (1 << 30)) return CDGRAB_EINVAL;
     plan->pairs = m * (n / 2);
     plan->block_pairs = pick_block_pairs(plan->pairs, block_pairs);
     plan->blocks = (plan->pairs + plan->block_pairs - 1) / plan->block_pairs;
     plan->vector_width = pick_vector_width(d, streamed ? 256 : base_align);
-    int64_t ntiles = (d + kTileE - 1) / kTileE;
-    int64_t want = pass1_groups_opt > 0 ? pass1_groups_opt : (int64_t)num_cu * 4;
+    // long rows stream through 128-element tiles with two resident workgroups per CU;
+    // short rows use 64-element tiles so that more workgroups share the work
+    plan->tile_elems = (d >= (int64_t)128 * 2 * num_cu) ? 128 : 64;
+    int64_t ntiles = (d + plan->tile_elems - 1) / plan->tile_elems;
+    int64_t want = pass1_groups_opt > 0 ? pass1_groups_opt
+                                        : (int64_t)num_cu * (plan->tile_elems == 128 ? 2 : 4);
     plan->pass1_groups = (int32_t)std::max<int64_t>(1, std::min<int64_t>(want, ntiles));
     plan->pass2_groups = (int32_t)((d + kThreads * 4 - 1) / (kThreads * 4));
     plan->staging_bytes = streamed ? (int64_t)plan->block_pairs * 2 * d * 4 : 0;
-    plan->workspace_bytes = round_up(d, kTileE) * 8 +
+    plan->workspace_bytes = round_up(d, kPadE) * 8 +
                             (int64_t)plan->pass1_groups * part_size(plan->block_pairs) * 8 +
                             plan->staging_bytes;
     plan->bytes_per_example = 8.0 * (double)d + 12.0 * (double)d / plan->block_pairs;
@@ -147,36 +151,46 @@ int ensure(cdgrab_handle *h, T *&ptr, int64_t &cap, int64_t want) {
 }
 
 template <int BB, int VW>
-void launch_pass1(cdgrab_handle *h, const RowMap &rm, int groups, int64_t ntiles) {
-    hipLaunchKernelGGL((pass1_dots_gram<BB, VW>), dim3(groups), dim3(kThreads), 0, h->stream, rm,
-                       h->r_sum, h->partials, ntiles);
+void launch_pass1(cdgrab_handle *h, const RowMap &rm, const cdgrab_plan &plan) {
+    if (plan.tile_elems == 128) {
+        int64_t ntiles = (rm.d + 127) / 128;
+        hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 128>), dim3(plan.pass1_groups), dim3(kThreads), 0,
+                           h->stream, rm, h->r_sum, h->partials, ntiles);
+    } else {
+        int64_t ntiles = (rm.d + 63) / 64;
+        hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 64>), dim3(plan.pass1_groups), dim3(kThreads), 0,
+                           h->stream, rm, h->r_sum, h->partials, ntiles);
+    }
 }
 template <int BB, int VW>
 void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
-    hipLaunchKernelGGL((pass2_apply<BB, VW>), dim3(groups), dim3(kThreads), 0, h->stream, rm,
-                       h->eps_blk, h->r_sum);
+    if (rm.nb == BB)
+        hipLaunchKernelGGL((pass2_apply<BB, VW, true>), dim3(groups), dim3(kThreads), 0, h->stream, rm,
+                           h->eps_blk, h->r_sum);
+    else
+        hipLaunchKernelGGL((pass2_apply<BB, VW, false>), dim3(groups), dim3(kThreads), 0, h->stream, rm,
+                           h->eps_blk, h->r_sum);
 }
 template <int BB>
 void launch_resolve(cdgrab_handle *h, const RowMap &rm, int8_t *signs_out, double *dots_out) {
-    hipLaunchKernelGGL((resolve_signs<BB>), dim3(1), dim3(64), 0, h->stream, h->reduced, rm.nb,
-                       rm.p0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out);
+    hipLaunchKernelGGL((resolve_signs<BB>), dim3(1), dim3(kThreads), 0, h->stream, h->reduced, rm.nb,
+                       rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out);
 }
 
 template <int BB>
 int run_block_vw(cdgrab_handle *h, const RowMap &rm, const cdgrab_plan &plan, int8_t *signs_out,
                  double *dots_out) {
-    const int64_t ntiles = (rm.d + kTileE - 1) / kTileE;
     const int part = PartLayout<BB>::PART;
     MARK(h, 2, kPass1);
     switch (plan.vector_width) {
-        case 4: launch_pass1<BB, 4>(h, rm, plan.pass1_groups, ntiles); break;
-        case 2: launch_pass1<BB, 2>(h, rm, plan.pass1_groups, ntiles); break;
-        default: launch_pass1<BB, 1>(h, rm, plan.pass1_groups, ntiles); break;
+        case 4: launch_pass1<BB, 4>(h, rm, plan); break;
+        case 2: launch_pass1<BB, 2>(h, rm, plan); break;
+        default: launch_pass1<BB, 1>(h, rm, plan); break;
     }
     MARK(h, 2, kReduce);
-    hipLaunchKernelGGL(reduce_partials, dim3((part + kReduceEntries - 1) / kReduceEntries),
-                       dim3(kThreads), 0, h->stream, h->partials, h->reduced, part,
-                       plan.pass1_groups);
+    hipLaunchKernelGGL(reduce_partials,
+                       dim3((part + kReduceEntries - 1) / kReduceEntries, kReduceSlices),
+                       dim3(kThreads), 0, h->stream, h->partials, h->reduced, part, plan.pass1_groups);
     MARK(h, 2, kResolve);
     launch_resolve<BB>(h, rm, signs_out, dots_out);
     MARK(h, 2, kPass2);
@@ -295,11 +309,11 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
 
     // workspace
     int64_t fixed_cap = 0;
-    rc = ensure(h, h->r_sum, h->r_cap, round_up(d, kTileE));
+    rc = ensure(h, h->r_sum, h->r_cap, round_up(d, kPadE));
     if (rc) return rc;
     rc = ensure(h, h->partials, h->partials_cap, (int64_t)plan.pass1_groups * part_size(bb));
     if (rc) return rc;
-    if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)PartLayout<32>::PART); if (rc) return rc; }
+    if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)kReduceSlices * PartLayout<32>::PART); if (rc) return rc; }
     if (!h->eps_blk) { fixed_cap = 0; rc = ensure(h, h->eps_blk, fixed_cap, (int64_t)32); if (rc) return rc; }
     if (streamed) { rc = ensure(h, h->staging, h->staging_cap, (int64_t)bb * 2 * d); if (rc) return rc; }
 
@@ -311,18 +325,20 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
                        h->stream, h->r_sum, h->r_cap);
 
     RowMap rm;
-    rm.d = d; rm.m = m; rm.n = n;
+    rm.d = d; rm.m = (int32_t)m; rm.n = n;
     rm.dense = streamed ? 0 : 1;
     rm.base = streamed ? h->staging : grads;
     for (int64_t blk = 0; blk < plan.blocks; ++blk) {
-        rm.p0 = blk * bb;
-        rm.nb = (int32_t)std::min<int64_t>(bb, plan.pairs - rm.p0);
+        const int64_t p0 = blk * bb;
+        rm.k0 = p0 / m;
+        rm.i0 = (int32_t)(p0 - rm.k0 * m);
+        rm.nb = (int32_t)std::min<int64_t>(bb, plan.pairs - p0);
         if (streamed) {
             MARK(h, 1, kGen);
-            int grc = gen(gen_ctx, rm.p0, rm.nb, h->staging, h->stream);
+            int grc = gen(gen_ctx, p0, rm.nb, h->staging, h->stream);
             if (grc != 0)
                 return fail(h, CDGRAB_EGEN, "generator callback returned %d at pair %lld", grc,
-                            (long long)rm.p0);
+                            (long long)p0);
         }
         MARK(h, 1, kBalance);
         rc = (bb == 32) ? run_block_vw<32>(h, rm, plan, signs_out, dots_out)

@@ -80,6 +80,8 @@ def _hip_lib():
         lib.synth_fill_pairs_device.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                                 ctypes.c_void_p, ctypes.c_void_p]
         lib.synth_fill_pairs_device.restype = ctypes.c_int
+        lib.synth_set_drain.argtypes = [ctypes.c_void_p, ctypes.c_int64]
+        lib.synth_set_drain.restype = ctypes.c_int
         _hip = lib
     return _hip
 
@@ -87,6 +89,25 @@ def _hip_lib():
 def mix(x: int) -> int:
     """The generator's 64-bit mixing function (for its statistical tests)."""
     return int(_host_lib().synth_mix_host(ctypes.c_uint64(x & (2 ** 64 - 1))))
+
+
+_drain_buf = None
+
+
+def set_input_drain(enabled: bool, device: str = "cuda:0", megabytes: int = 384) -> None:
+    """After every device fill, read a zero-filled scratch buffer larger than the
+    GPU's last-level cache (256 MB Infinity Cache + L2), so that the rows just
+    written have reached HBM before the consumer starts.  The drain runs inside the
+    generator's own (separately timed) work."""
+    global _drain_buf
+    import torch
+    lib = _hip_lib()
+    if enabled:
+        if _drain_buf is None:
+            _drain_buf = torch.zeros(megabytes * (1 << 20) // 4, dtype=torch.float32, device=device)
+        lib.synth_set_drain(_drain_buf.data_ptr(), _drain_buf.numel())
+    else:
+        lib.synth_set_drain(None, 0)
 
 
 class SynthRows:
