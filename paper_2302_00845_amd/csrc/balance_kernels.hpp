@@ -316,19 +316,31 @@ __global__ __launch_bounds__(kThreads) void resolve_signs(const double *__restri
     __syncthreads();
     if (threadIdx.x >= 64) return;
     const int lane = threadIdx.x;
+    // lane k keeps column k of the Gram matrix (= row k, it is symmetric) in registers
+    double col[BB];
+#pragma unroll
+    for (int j = 0; j < BB; ++j) col[j] = (lane < BB) ? G[lane][j] : 0.0;
     double t = (lane < nb) ? P[lane] : 0.0;
-    for (int j = 0; j < nb; ++j) {
-        double tj = __shfl(t, j, 64);
-        int eps = (tj <= 0.0) ? 1 : -1;
-        if (lane == j) {
-            uint32_t q = (uint32_t)(i0 + j);
-            uint32_t dk = q / (uint32_t)m;
-            int64_t i = q - dk * (uint32_t)m, k = k0 + dk;
-            eps_blk[j] = (int8_t)eps;
-            signs_out[i * half_n + k] = (int8_t)eps;
-            if (dots_out) dots_out[i * half_n + k] = tj;
+    double my_t = 0.0;
+    int my_eps = 0;
+#pragma unroll
+    for (int j = 0; j < BB; ++j) {
+        if (j < nb) {  // uniform
+            const int lo = __builtin_amdgcn_readlane(__double2loint(t), j);
+            const int hi = __builtin_amdgcn_readlane(__double2hiint(t), j);
+            const double tj = __hiloint2double(hi, lo);
+            const int eps = (tj <= 0.0) ? 1 : -1;
+            if (lane == j) { my_t = tj; my_eps = eps; }
+            if (lane > j) t += (double)eps * col[j];
         }
-        if (lane > j && lane < nb) t += (double)eps * G[j][lane];
+    }
+    if (lane < nb) {
+        uint32_t q = (uint32_t)(i0 + lane);
+        uint32_t dk = q / (uint32_t)m;
+        int64_t i = q - dk * (uint32_t)m, k = k0 + dk;
+        eps_blk[lane] = (int8_t)my_eps;
+        signs_out[i * half_n + k] = (int8_t)my_eps;
+        if (dots_out) dots_out[i * half_n + k] = my_t;
     }
 }
 
@@ -363,6 +375,47 @@ __global__ __launch_bounds__(kThreads) void pass2_apply(RowMap rm, const int8_t 
     lo.x += acc[0]; lo.y += acc[1]; hi.x += acc[2]; hi.y += acc[3];
     *reinterpret_cast<double2 *>(r_sum + e) = lo;
     *reinterpret_cast<double2 *>(r_sum + e + 2) = hi;
+}
+
+// ---------------------------------------------------------------------------
+// Pass 2 for short rows: the block's pairs are split over the four waves of a
+// workgroup (each wave sums BB/4 pairs for 256 consecutive elements), the four
+// partial sums are added in wave order through LDS, and 256 threads update one
+// element each.  Four times the workgroups and a quarter of the loads per thread
+// of the flat form, which is what a latency-bound launch needs.
+template <int BB, int VW>
+__global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const int8_t *__restrict__ eps_blk,
+                                                              double *__restrict__ r_sum)
+{
+    __shared__ double part[kWaves][256];
+    const int64_t d = rm.d;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t e = (int64_t)blockIdx.x * 256 + lane * 4;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    constexpr int PER = BB / kWaves;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int j = wave * PER + q;
+        if (j < rm.nb) {
+            float4 a = load4<VW>(rm.row(j, 0), e, d);
+            float4 b = load4<VW>(rm.row(j, 1), e, d);
+            double sg = (double)eps_blk[j];
+            acc[0] = __builtin_fma(sg, (double)b.x - (double)a.x, acc[0]);
+            acc[1] = __builtin_fma(sg, (double)b.y - (double)a.y, acc[1]);
+            acc[2] = __builtin_fma(sg, (double)b.z - (double)a.z, acc[2]);
+            acc[3] = __builtin_fma(sg, (double)b.w - (double)a.w, acc[3]);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) part[wave][lane * 4 + q] = acc[q];
+    __syncthreads();
+    const int64_t mine = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (mine < d) {
+        double sum = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) sum += part[w][threadIdx.x];
+        r_sum[mine] += sum;
+    }
 }
 
 // ---------------------------------------------------------------------------

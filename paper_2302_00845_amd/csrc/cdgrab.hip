@@ -164,6 +164,12 @@ void launch_pass1(cdgrab_handle *h, const RowMap &rm, const cdgrab_plan &plan) {
 }
 template <int BB, int VW>
 void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
+    // short rows: too few flat workgroups to hide latency -> split the pairs over waves
+    if (groups < 2 * h->num_cu) {
+        hipLaunchKernelGGL((pass2_apply_split<BB, VW>), dim3((unsigned)((rm.d + 255) / 256)), dim3(kThreads),
+                           0, h->stream, rm, h->eps_blk, h->r_sum);
+        return;
+    }
     if (rm.nb == BB)
         hipLaunchKernelGGL((pass2_apply<BB, VW, true>), dim3(groups), dim3(kThreads), 0, h->stream, rm,
                            h->eps_blk, h->r_sum);
