@@ -71,9 +71,12 @@ def test_c5_full_d_block_and_ragged_tail(lib):
     print("in-margin flips:", flips)
 
 
-def test_c4_whole_epoch_properties(lib):
-    """The benchmark's configuration: full C4 epoch (16 384 examples, d=11.2M)."""
-    w = workloads.CONFIGS["c4_resnet18"]
+@pytest.mark.parametrize("name", ["c3_stream_1m", "c4_resnet18", "c5_gpt2s"])
+def test_whole_epoch_properties(lib, name):
+    """The benchmark's configuration (full n, full d, default launch plan) of each
+    streamed workload: properties that hold at any size, and the running sum at
+    sampled coordinates against rows regenerated element by element on the host."""
+    w = workloads.CONFIGS[name]
     g = synth.from_workload(w, 2302)
     fn, ctx = g.device_callback()
     h = lib.Handle(timing=1)
@@ -89,7 +92,8 @@ def test_c4_whole_epoch_properties(lib):
     assert np.array_equal(expected_perm_from_signs(signs, perm_in), out["perm"].cpu().numpy())
     # running sum at sampled coordinates = signed sum of regenerated differences
     rng = np.random.default_rng(0)
-    elems = np.unique(np.concatenate([[0, 1, w.d - 1, 174_999, 175_000],
+    blk = g.block_len
+    elems = np.unique(np.concatenate([[0, 1, w.d - 1, blk - 1, min(blk, w.d - 1)],
                                       rng.integers(0, w.d, 59)])).astype(np.int64)
     all_rows = np.arange(w.m * w.n, dtype=np.int64)
     vals = g.sample_host(all_rows, elems).astype(np.float64).reshape(w.m, w.n, -1)
@@ -97,8 +101,8 @@ def test_c4_whole_epoch_properties(lib):
     want = (signs[:, :, None].astype(np.float64) * diffs).sum((0, 1))
     got = out["r64"].cpu().numpy()[elems]
     np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12 * np.abs(diffs).sum((0, 1)).max())
-    # greedy bound at the end of the epoch on the sampled coordinates is not checkable
-    # (it is a statement about full norms); the balance it buys is: |r| grows like a
-    # random walk at worst
+    # the balanced sum stays far below a random-sign walk's worst case
     assert np.abs(got).max() < 50 * np.sqrt(w.m * w.n / 2) * np.abs(diffs).std()
-    print(h.timing())
+    r32 = out["r32"].cpu().numpy()[elems]
+    np.testing.assert_allclose(r32, want, rtol=1e-6, atol=1e-6 * np.abs(want).max())
+    print(name, h.timing())

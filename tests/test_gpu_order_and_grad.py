@@ -73,3 +73,29 @@ def test_pergrad_empty_and_errors(lib):
     assert lib.cdgrab_pergrad(h, X, y, W).shape == (0, 18)
     with pytest.raises(TypeError):
         lib.cdgrab_pergrad(h, X.double(), y, W)
+
+
+def test_config2_softmax_end_to_end(lib):
+    """Config 2 at full size: 60 000 per-example gradients of the 784->10 softmax
+    regression on the GPU (<= 1e-5 rel. L2 per example against the double oracle),
+    then one balanced epoch on those gradients, judged against the oracle walking
+    the same bytes."""
+    from parity import check_epoch
+    w = workloads.CONFIGS["c2_softmax"]
+    N = w.m * w.n
+    X, y, W = workloads.softmax_problem(7, N)
+    h = lib.Handle()
+    G = lib.cdgrab_pergrad(h, torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(),
+                           torch.from_numpy(W).cuda())
+    perm_in = workloads.random_perms(8, w.m, w.n)
+    out = lib.cdgrab_balance_epoch(h, w.m, w.n, w.d, grads=G.view(w.m, w.n, w.d),
+                                   perm_in=torch.from_numpy(perm_in).cuda(), want_r64=True, want_dots=True)
+    torch.cuda.synchronize()
+    Gh = G.cpu().numpy()
+    want = oracle.softmax_pergrad(X, y, W)
+    num = np.linalg.norm(Gh.astype(np.float64) - want, axis=1)
+    den = np.linalg.norm(want.astype(np.float64), axis=1)
+    assert np.all(num <= 1e-5 * den)
+    got = {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
+    rep = check_epoch(Gh.reshape(w.m, w.n, w.d), got, perm_in)
+    print(rep)
