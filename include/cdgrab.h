@@ -159,6 +159,16 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
 int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,
                    const int32_t *perm_in, int32_t *perm_out);
 
+/* Parallel herding objective of a set of vectors under given per-worker orders
+ * (Sec. 3.2, the quantity PairBalance + Reorder drive down; Lemma 1):
+ *     max_{k<=n} || sum_{j<=k} sum_{i<m} ( z[i][perm[i][j]] - zbar ) ||_inf,
+ *     zbar = mean of all m*n vectors.
+ *   z [m][n][d] fp32 dev, indexed by example id (NOT by visiting position),
+ *   perm [m][n] int32 dev or NULL (identity), bound_out: one double, dev.
+ * Sums in double.  Errors: EINVAL (sizes, null), ENOMEM, EHIP. */
+int cdgrab_herding_bound(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *z,
+                         const int32_t *perm, double *bound_out);
+
 /* Timings of the last cdgrab_balance_epoch on this handle (options.timing >= 1).
  * Synchronises the stream.  Errors: EINVAL (timing was off), EHIP. */
 int cdgrab_get_timing(cdgrab_handle *h, cdgrab_timing *out /*host*/);

@@ -8,6 +8,7 @@ from .cdgrab import (  # noqa: F401
     CdgrabError,
     Handle,
     cdgrab_balance_epoch,
+    cdgrab_herding_bound,
     cdgrab_pergrad,
     cdgrab_plan_epoch,
     cdgrab_reorder,

@@ -86,6 +86,8 @@ def load_library():
     lib.cdgrab_balance_epoch.restype = ctypes.c_int
     lib.cdgrab_reorder.argtypes = [P, i64, i64, P, P, P]
     lib.cdgrab_reorder.restype = ctypes.c_int
+    lib.cdgrab_herding_bound.argtypes = [P, i64, i64, i64, P, P, P]
+    lib.cdgrab_herding_bound.restype = ctypes.c_int
     lib.cdgrab_get_timing.argtypes = [P, ctypes.POINTER(Timing)]
     lib.cdgrab_get_timing.restype = ctypes.c_int
     _lib = lib
@@ -211,4 +213,15 @@ def cdgrab_reorder(h: Handle, signs: torch.Tensor, perm_in: Optional[torch.Tenso
     h._check(h._lib.cdgrab_reorder(
         h._h, m, n, _ptr(signs, torch.int8, (m, n), "signs", h.device),
         _ptr(perm_in, torch.int32, (m, n), "perm_in", h.device), out.data_ptr()))
+    return out
+
+
+def cdgrab_herding_bound(h: Handle, z: torch.Tensor, perm: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Parallel herding objective of z[m][n][d] (indexed by example id) visited in
+    the orders perm[m][n]; returns a one-element float64 GPU tensor."""
+    m, n, d = z.shape
+    out = torch.empty((1,), dtype=torch.float64, device=h.device)
+    h._check(h._lib.cdgrab_herding_bound(
+        h._h, m, n, d, _ptr(z, torch.float32, (m, n, d), "z", h.device),
+        _ptr(perm, torch.int32, (m, n), "perm", h.device), out.data_ptr()))
     return out

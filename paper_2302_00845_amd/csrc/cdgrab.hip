@@ -15,6 +15,7 @@
 
 #include "balance_kernels.hpp"
 #include "order_kernels.hpp"
+#include "herding_kernels.hpp"
 
 using namespace cdgrab;
 
@@ -45,6 +46,7 @@ struct cdgrab_handle {
     double *reduced = nullptr;                            // kReduceSlices x PartLayout<32>::PART doubles
     int8_t *eps_blk = nullptr;                            // 32 signs
     int32_t *flag = nullptr;                              // reorder's bad-sign flag
+    double *herd_ws = nullptr; int64_t herd_cap = 0;      // herding evaluator: segment sums, starts, mean
     float *staging = nullptr;  int64_t staging_cap = 0;   // floats
 
     std::vector<hipEvent_t> event_pool;
@@ -252,6 +254,7 @@ int cdgrab_destroy(cdgrab_handle *h) {
     if (h->reduced) (void)hipFree(h->reduced);
     if (h->eps_blk) (void)hipFree(h->eps_blk);
     if (h->flag) (void)hipFree(h->flag);
+    if (h->herd_ws) (void)hipFree(h->herd_ws);
     if (h->staging) (void)hipFree(h->staging);
     delete h;
     return CDGRAB_OK;
@@ -386,6 +389,35 @@ int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,
     HIP_TRY(h, hipMemcpyAsync(&bad, h->flag, sizeof bad, hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     if (bad) return fail(h, CDGRAB_EINVAL, "cdgrab_reorder: a sign is neither +1 nor -1");
+    return CDGRAB_OK;
+}
+
+int cdgrab_herding_bound(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *z,
+                         const int32_t *perm, double *bound_out) {
+    if (!h) return CDGRAB_EINVAL;
+    if (m < 1 || n < 1 || d < 1 || m > (INT64_MAX / n) / d)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_herding_bound: need m>=1, n>=1, d>=1");
+    if (!z || !bound_out) return fail(h, CDGRAB_EINVAL, "cdgrab_herding_bound: null pointer");
+    HIP_TRY(h, hipSetDevice(h->device));
+    HerdingShape sh;
+    sh.m = m; sh.n = n; sh.d = d;
+    // enough (segment, element) threads to fill the chip, at least one step per segment
+    int64_t want_threads = (int64_t)h->num_cu * 2048;
+    int64_t segs = std::max<int64_t>(1, std::min<int64_t>(n, (want_threads + d - 1) / d));
+    sh.seg_len = (n + segs - 1) / segs;
+    sh.segments = (n + sh.seg_len - 1) / sh.seg_len;
+    int rc = ensure(h, h->herd_ws, h->herd_cap, 2 * sh.segments * d + d);
+    if (rc) return rc;
+    double *segsum = h->herd_ws, *start = segsum + sh.segments * d, *zbar = start + sh.segments * d;
+    const int64_t threads = sh.segments * d;
+    const unsigned grid = (unsigned)((threads + 255) / 256);
+    unsigned long long *bits = reinterpret_cast<unsigned long long *>(bound_out);
+    hipLaunchKernelGGL(herding_clear, dim3(1), dim3(1), 0, h->stream, bits);
+    hipLaunchKernelGGL(herding_segment_sums, dim3(grid), dim3(256), 0, h->stream, z, perm, sh, segsum);
+    hipLaunchKernelGGL(herding_segment_offsets, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, h->stream,
+                       segsum, sh, zbar, start);
+    hipLaunchKernelGGL(herding_prefix_max, dim3(grid), dim3(256), 0, h->stream, z, perm, sh, zbar, start, bits);
+    HIP_TRY(h, hipGetLastError());
     return CDGRAB_OK;
 }
 

@@ -91,3 +91,13 @@ def random_signs(seed: int, m: int, n: int) -> np.ndarray:
     """Per-example +-1 signs [m][n], int8."""
     rng = np.random.default_rng(seed)
     return (2 * rng.integers(0, 2, size=(m, n)) - 1).astype(np.int8)
+
+
+def herding_vectors(seed: int, N: int, d: int = 16) -> np.ndarray:
+    """The vectors of the paper's synthetic herding-bound study (App. E): N draws
+    from Unif(0,1)^d, zero-centred over the set, each scaled to unit L2 norm."""
+    rng = np.random.default_rng(seed)
+    z = rng.random((N, d))
+    z -= z.mean(axis=0, keepdims=True)
+    z /= np.linalg.norm(z, axis=1, keepdims=True)
+    return z.astype(np.float32)
