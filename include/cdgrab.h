@@ -149,6 +149,27 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                          int32_t *perm_out, float *r_out, double *r64_out,
                          double *dots_out);
 
+/* One training epoch of the softmax-regression model under CD-GraB ("CD-GraB
+ * Workers" + "CD-GraB Parameter Server", Sec. 3.3), the m workers simulated on one
+ * GPU.  For step j = 0 .. n-1: worker i computes the gradient of example
+ * perm_in[i][j] at the current weights, the server averages the m gradients and
+ * every worker applies  v <- momentum v + gbar;  W <- W - lr v.  After every second
+ * step the m new pairs are balanced in worker order exactly as in
+ * cdgrab_balance_epoch, whose outputs signs_out / perm_out have the same meaning.
+ *   X [m][n][in_dim] fp32 dev (example j of worker i is row (i, j)), y [m][n] int32 dev,
+ *   perm_in [m][n] int32 dev or NULL, W [(in_dim+1)][classes] fp32 dev (in/out),
+ *   velocity [(in_dim+1)*classes] fp32 dev (in/out) or NULL when momentum == 0,
+ *   grads_out [m][n][(in_dim+1)*classes] fp32 dev or NULL: the gradient rows in
+ *     visiting order (for verification; the epoch itself keeps only a few steps' rows),
+ *   loss_out [m][n] fp32 dev or NULL: loss of each example when it was visited.
+ * fp32 model arithmetic, double balancing arithmetic.
+ * Errors: EINVAL (sizes, n odd, null, momentum without velocity), ENOMEM, EHIP. */
+int cdgrab_train_epoch_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t in_dim,
+                               int64_t classes, const float *X, const int32_t *y,
+                               const int32_t *perm_in, float *W, float *velocity, float lr,
+                               float momentum, int8_t *signs_out, int32_t *perm_out,
+                               float *grads_out, float *loss_out);
+
 /* Reorder from arbitrary per-example signs ("Reordering Vectors based on Balanced
  * Signs", Sec. 2.1), one independent problem per worker:
  *   perm_out[i] = concat(L_pos, reverse(L_neg)), L_pos / L_neg the entries of

@@ -56,6 +56,8 @@ def _load():
     lib.oracle_softmax_loss.restype = dbl
     lib.oracle_parallel_herding.argtypes = [i64, i64, i64, P, P]
     lib.oracle_parallel_herding.restype = dbl
+    lib.oracle_train_epoch_softmax.argtypes = [i64, i64, i64, i64, P, P, P, P, P, dbl, dbl, P, P]
+    lib.oracle_train_epoch_softmax.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -175,3 +177,26 @@ def parallel_herding(z: np.ndarray, perm: np.ndarray | None = None) -> float:
         perm = _c(perm, np.int32)
         assert perm.shape == (m, n)
     return _load().oracle_parallel_herding(m, n, d, _p(z), _p(perm))
+
+
+def train_epoch_softmax(X: np.ndarray, y: np.ndarray, perm_in: np.ndarray | None, W: np.ndarray,
+                        v: np.ndarray | None, lr: float, momentum: float):
+    """One training epoch of m simulated workers (see the C function).  X[m][n][in_dim],
+    y[m][n]; W, v double arrays, not modified.  Returns dict W, v (double), rows
+    [m][n][d] fp32, loss [m][n], and the balancing of those rows (eps, perm, r)."""
+    X = _c(X, np.float32)
+    y = _c(y, np.int32)
+    m, n, in_dim = X.shape
+    W = np.array(W, dtype=np.float64, order="C").copy()
+    classes = W.shape[1]
+    v = np.zeros(W.size) if v is None else np.array(v, dtype=np.float64).reshape(-1).copy()
+    if perm_in is not None:
+        perm_in = _c(perm_in, np.int32)
+    rows = np.zeros((m, n, W.size), np.float32)
+    loss = np.zeros((m, n), np.float64)
+    rc = _load().oracle_train_epoch_softmax(m, n, in_dim, classes, _p(X), _p(y), _p(perm_in), _p(W),
+                                            _p(v), float(lr), float(momentum), _p(rows), _p(loss))
+    if rc != 0:
+        raise ValueError("oracle_train_epoch_softmax failed")
+    bal = server_epoch(rows, perm_in)
+    return {"W": W, "v": v, "rows": rows, "loss": loss, "eps": bal["eps"], "perm": bal["perm"], "r": bal["r"]}

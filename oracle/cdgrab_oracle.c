@@ -32,6 +32,10 @@
  *                             linear model (the per-example gradient a worker
  *                             computes in "CD-GraB Workers", line 4).
  *   oracle_parallel_herding   the parallel herding objective (Sec. 3.2).
+ *   oracle_train_epoch_softmax  "CD-GraB Workers" + "CD-GraB Parameter Server"
+ *                             (Sec. 3.3) for the softmax-regression model: per
+ *                             step, m per-example gradients at the current
+ *                             weights, their average, one SGD(+momentum) update.
  *
  * Readings of the paper taken here (each is also pinned by a test):
  *   - Sign exported per pair.  The paper balances c = z1 - z2 and calls the
@@ -319,4 +323,60 @@ double oracle_parallel_herding(int64_t m, int64_t n, int64_t d, const float *z,
     }
     free(zbar); free(acc);
     return best;
+}
+
+/* ------------------------------------------------------------------------- */
+/* One training epoch of m simulated workers on the softmax-regression model.
+ *   X [m][n][in_dim], y [m][n], perm_in [m][n] or NULL (identity)
+ *   W [(in_dim+1)*classes] double, in/out;  v [same] double, in/out (velocity)
+ *   rows_out [m][n][d] fp32: gradient of worker i at step j, in visiting order
+ *   loss_out [m][n] or NULL: loss of the visited example at the weights it saw
+ * Step j (workers' lines 4-7, server's lines 5-7): every worker takes the gradient
+ * of example perm_in[i][j] at the current W; gbar = mean over workers;
+ * v <- momentum v + gbar; W <- W - lr v (the update rule of the paper's
+ * experiments, SGD with momentum).  The server's balancing of these rows does not
+ * feed back into the epoch (the sign list is only used for the next epoch's order),
+ * so the caller runs oracle_server_epoch on rows_out. */
+int oracle_train_epoch_softmax(int64_t m, int64_t n, int64_t in_dim, int64_t classes,
+                               const float *X, const int32_t *y, const int32_t *perm_in,
+                               double *W, double *v, double lr, double momentum,
+                               float *rows_out, double *loss_out)
+{
+    if (m < 1 || n < 1 || in_dim < 1 || classes < 1) return -1;
+    const int64_t d = (in_dim + 1) * classes;
+    double *delta = (double *)malloc((size_t)classes * sizeof(double));
+    double *gbar = (double *)malloc((size_t)d * sizeof(double));
+    if (!delta || !gbar) { free(delta); free(gbar); return -1; }
+    for (int64_t j = 0; j < n; ++j) {
+        for (int64_t p = 0; p < d; ++p) gbar[p] = 0.0;
+        for (int64_t i = 0; i < m; ++i) {
+            int64_t id = perm_in ? perm_in[i * n + j] : j;
+            const float *x = X + (i * n + id) * in_dim;
+            int32_t label = y[i * n + id];
+            double mx = -INFINITY, Z = 0.0;
+            for (int64_t c = 0; c < classes; ++c) {
+                double a = W[in_dim * classes + c];
+                for (int64_t r = 0; r < in_dim; ++r) a += (double)x[r] * W[r * classes + c];
+                delta[c] = a;
+                if (a > mx) mx = a;
+            }
+            for (int64_t c = 0; c < classes; ++c) Z += exp(delta[c] - mx);
+            if (loss_out) loss_out[i * n + j] = -(delta[label] - mx - log(Z));
+            for (int64_t c = 0; c < classes; ++c)
+                delta[c] = exp(delta[c] - mx) / Z - (c == label ? 1.0 : 0.0);
+            float *row = rows_out + (i * n + j) * d;
+            for (int64_t r = 0; r <= in_dim; ++r)
+                for (int64_t c = 0; c < classes; ++c) {
+                    double g = (r < in_dim ? (double)x[r] : 1.0) * delta[c];
+                    row[r * classes + c] = (float)g;
+                    gbar[r * classes + c] += g;
+                }
+        }
+        for (int64_t p = 0; p < d; ++p) {
+            v[p] = momentum * v[p] + gbar[p] / (double)m;
+            W[p] -= lr * v[p];
+        }
+    }
+    free(delta); free(gbar);
+    return 0;
 }

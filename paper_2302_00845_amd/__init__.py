@@ -12,6 +12,7 @@ from .cdgrab import (  # noqa: F401
     cdgrab_pergrad,
     cdgrab_plan_epoch,
     cdgrab_reorder,
+    cdgrab_train_epoch_softmax,
     library_path,
     load_library,
 )

@@ -86,6 +86,9 @@ def load_library():
     lib.cdgrab_balance_epoch.restype = ctypes.c_int
     lib.cdgrab_reorder.argtypes = [P, i64, i64, P, P, P]
     lib.cdgrab_reorder.restype = ctypes.c_int
+    lib.cdgrab_train_epoch_softmax.argtypes = [P, i64, i64, i64, i64, P, P, P, P, P, ctypes.c_float,
+                                               ctypes.c_float, P, P, P, P]
+    lib.cdgrab_train_epoch_softmax.restype = ctypes.c_int
     lib.cdgrab_herding_bound.argtypes = [P, i64, i64, i64, P, P, P]
     lib.cdgrab_herding_bound.restype = ctypes.c_int
     lib.cdgrab_get_timing.argtypes = [P, ctypes.POINTER(Timing)]
@@ -225,3 +228,30 @@ def cdgrab_herding_bound(h: Handle, z: torch.Tensor, perm: Optional[torch.Tensor
         h._h, m, n, d, _ptr(z, torch.float32, (m, n, d), "z", h.device),
         _ptr(perm, torch.int32, (m, n), "perm", h.device), out.data_ptr()))
     return out
+
+
+def cdgrab_train_epoch_softmax(h: Handle, X: torch.Tensor, y: torch.Tensor, W: torch.Tensor,
+                               perm_in: Optional[torch.Tensor] = None,
+                               velocity: Optional[torch.Tensor] = None, lr: float = 0.1,
+                               momentum: float = 0.0, want_grads: bool = False,
+                               want_loss: bool = True) -> dict:
+    """One CD-GraB training epoch of the softmax-regression model; W (and velocity)
+    are updated in place.  X[m][n][in_dim], y[m][n]."""
+    m, n, in_dim = X.shape
+    classes = W.shape[1]
+    d = (in_dim + 1) * classes
+    dev = h.device
+    signs = torch.empty((m, n // 2), dtype=torch.int8, device=dev)
+    perm = torch.empty((m, n), dtype=torch.int32, device=dev)
+    grads = torch.empty((m, n, d), dtype=torch.float32, device=dev) if want_grads else None
+    loss = torch.empty((m, n), dtype=torch.float32, device=dev) if want_loss else None
+    h._check(h._lib.cdgrab_train_epoch_softmax(
+        h._h, m, n, in_dim, classes,
+        _ptr(X, torch.float32, (m, n, in_dim), "X", dev), _ptr(y, torch.int32, (m, n), "y", dev),
+        _ptr(perm_in, torch.int32, (m, n), "perm_in", dev),
+        _ptr(W, torch.float32, (in_dim + 1, classes), "W", dev),
+        _ptr(velocity, torch.float32, (d,), "velocity", dev), lr, momentum,
+        signs.data_ptr(), perm.data_ptr(),
+        grads.data_ptr() if grads is not None else None,
+        loss.data_ptr() if loss is not None else None))
+    return {"signs": signs, "perm": perm, "grads": grads, "loss": loss}

@@ -46,6 +46,7 @@ struct cdgrab_handle {
     double *reduced = nullptr;                            // kReduceSlices x PartLayout<32>::PART doubles
     int8_t *eps_blk = nullptr;                            // 32 signs
     int32_t *flag = nullptr;                              // reorder's bad-sign flag
+    float *train_delta = nullptr; int64_t train_delta_cap = 0;  // [m][classes] softmax deltas of one step
     double *herd_ws = nullptr; int64_t herd_cap = 0;      // herding evaluator: segment sums, starts, mean
     float *staging = nullptr;  int64_t staging_cap = 0;   // floats
 
@@ -255,6 +256,7 @@ int cdgrab_destroy(cdgrab_handle *h) {
     if (h->eps_blk) (void)hipFree(h->eps_blk);
     if (h->flag) (void)hipFree(h->flag);
     if (h->herd_ws) (void)hipFree(h->herd_ws);
+    if (h->train_delta) (void)hipFree(h->train_delta);
     if (h->staging) (void)hipFree(h->staging);
     delete h;
     return CDGRAB_OK;
@@ -288,10 +290,12 @@ int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
     return CDGRAB_OK;
 }
 
-int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *grads,
-                         cdgrab_gen_fn gen, void *gen_ctx, const int32_t *perm_in,
-                         int8_t *signs_out, int32_t *perm_out, float *r_out, double *r64_out,
-                         double *dots_out) {
+// One epoch.  With a generator, `chunk_pairs` flattened pairs are staged per callback
+// (0 = one block) and balanced block by block out of the staging buffer.
+static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *grads,
+                              cdgrab_gen_fn gen, void *gen_ctx, int64_t chunk_pairs,
+                              const int32_t *perm_in, int8_t *signs_out, int32_t *perm_out,
+                              float *r_out, double *r64_out, double *dots_out) {
     if (!h) return CDGRAB_EINVAL;
     if (m < 1 || n < 2 || (n & 1) || d < 1)
         return fail(h, CDGRAB_EINVAL,
@@ -324,7 +328,8 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
     if (rc) return rc;
     if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)kReduceSlices * PartLayout<32>::PART); if (rc) return rc; }
     if (!h->eps_blk) { fixed_cap = 0; rc = ensure(h, h->eps_blk, fixed_cap, (int64_t)32); if (rc) return rc; }
-    if (streamed) { rc = ensure(h, h->staging, h->staging_cap, (int64_t)bb * 2 * d); if (rc) return rc; }
+    if (chunk_pairs <= 0) chunk_pairs = bb;
+    if (streamed) { rc = ensure(h, h->staging, h->staging_cap, chunk_pairs * 2 * d); if (rc) return rc; }
 
     h->marks.clear();
     h->events_used = 0;
@@ -336,23 +341,27 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
     RowMap rm;
     rm.d = d; rm.m = (int32_t)m; rm.n = n;
     rm.dense = streamed ? 0 : 1;
-    rm.base = streamed ? h->staging : grads;
-    for (int64_t blk = 0; blk < plan.blocks; ++blk) {
-        const int64_t p0 = blk * bb;
-        rm.k0 = p0 / m;
-        rm.i0 = (int32_t)(p0 - rm.k0 * m);
-        rm.nb = (int32_t)std::min<int64_t>(bb, plan.pairs - p0);
+    rm.base = grads;
+    const int64_t chunk = streamed ? chunk_pairs : plan.pairs;
+    for (int64_t first = 0; first < plan.pairs; first += chunk) {
+        const int64_t cnt = std::min<int64_t>(chunk, plan.pairs - first);
         if (streamed) {
             MARK(h, 1, kGen);
-            int grc = gen(gen_ctx, p0, rm.nb, h->staging, h->stream);
+            int grc = gen(gen_ctx, first, cnt, h->staging, h->stream);
             if (grc != 0)
                 return fail(h, CDGRAB_EGEN, "generator callback returned %d at pair %lld", grc,
-                            (long long)p0);
+                            (long long)first);
         }
-        MARK(h, 1, kBalance);
-        rc = (bb == 32) ? run_block_vw<32>(h, rm, plan, signs_out, dots_out)
-                        : run_block_vw<16>(h, rm, plan, signs_out, dots_out);
-        if (rc) return rc;
+        for (int64_t p0 = first; p0 < first + cnt; p0 += bb) {
+            rm.k0 = p0 / m;
+            rm.i0 = (int32_t)(p0 - rm.k0 * m);
+            rm.nb = (int32_t)std::min<int64_t>(bb, first + cnt - p0);
+            if (streamed) rm.base = h->staging + (p0 - first) * 2 * d;
+            MARK(h, 1, kBalance);
+            rc = (bb == 32) ? run_block_vw<32>(h, rm, plan, signs_out, dots_out)
+                            : run_block_vw<16>(h, rm, plan, signs_out, dots_out);
+            if (rc) return rc;
+        }
     }
     MARK(h, 1, kFinish);
     {
@@ -366,11 +375,76 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
     MARK(h, 1, -1);
     HIP_TRY(h, hipGetLastError());
     h->last = cdgrab_timing{};
-    h->last.blocks = plan.blocks;
+    h->last.blocks = streamed ? ((plan.pairs / chunk) * ((chunk + bb - 1) / bb) +
+                                 ((plan.pairs % chunk) + bb - 1) / bb)
+                              : plan.blocks;
     h->last.block_pairs = bb;
     h->last.pass1_groups = plan.pass1_groups;
     h->have_timing = h->timing >= 1;
     return CDGRAB_OK;
+}
+
+int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *grads,
+                         cdgrab_gen_fn gen, void *gen_ctx, const int32_t *perm_in,
+                         int8_t *signs_out, int32_t *perm_out, float *r_out, double *r64_out,
+                         double *dots_out) {
+    return balance_epoch_impl(h, m, n, d, grads, gen, gen_ctx, 0, perm_in, signs_out, perm_out, r_out,
+                              r64_out, dots_out);
+}
+
+namespace {
+// State of the internal generator of cdgrab_train_epoch_softmax: it produces the rows
+// of a chunk of whole step pairs by running the workers' steps at the evolving weights.
+struct TrainCtx {
+    cdgrab_handle *h;
+    int64_t m, n, in_dim, classes, d;
+    const float *X; const int32_t *y; const int32_t *perm_in;
+    float *W, *velocity, *grads_out, *loss_out;
+    float lr, momentum;
+};
+
+int train_generate(void *vctx, int64_t first_pair, int64_t count, float *staging, void *stream) {
+    TrainCtx *c = static_cast<TrainCtx *>(vctx);
+    cdgrab_handle *h = c->h;
+    if (first_pair % c->m != 0 || count % c->m != 0) return 1;  // chunks are whole step pairs
+    const int64_t k_first = first_pair / c->m, k_count = count / c->m;
+    const size_t lds = (size_t)kGradWaves * (size_t)(c->in_dim + 1 + c->classes) * sizeof(float);
+    for (int64_t j = 2 * k_first; j < 2 * (k_first + k_count); ++j) {
+        hipLaunchKernelGGL(train_step_delta, dim3((unsigned)((c->m + kGradWaves - 1) / kGradWaves)),
+                           dim3(kGradWaves * 64), lds, static_cast<hipStream_t>(stream), c->X, c->y,
+                           c->perm_in, c->W, h->train_delta, c->loss_out, c->m, c->n, j, (int)c->in_dim,
+                           (int)c->classes);
+        hipLaunchKernelGGL(train_step_update, dim3((unsigned)((c->d + 255) / 256)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), c->X, c->perm_in, h->train_delta, c->W,
+                           c->velocity, staging, c->grads_out, c->m, c->n, j, k_first, (int)c->in_dim,
+                           (int)c->classes, c->lr, c->momentum);
+    }
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+}  // namespace
+
+int cdgrab_train_epoch_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t in_dim, int64_t classes,
+                               const float *X, const int32_t *y, const int32_t *perm_in, float *W,
+                               float *velocity, float lr, float momentum, int8_t *signs_out,
+                               int32_t *perm_out, float *grads_out, float *loss_out) {
+    if (!h) return CDGRAB_EINVAL;
+    if (m < 1 || n < 2 || (n & 1) || in_dim < 1 || classes < 1 || classes > 1024 || in_dim > (1 << 20))
+        return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: bad sizes");
+    if (!X || !y || !W || !signs_out || !perm_out)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: null pointer");
+    if (momentum != 0.0f && !velocity)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: momentum needs a velocity buffer");
+    if ((size_t)kGradWaves * (size_t)(in_dim + 1 + classes) * sizeof(float) > 64 * 1024)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: in_dim + classes too large for LDS staging");
+    HIP_TRY(h, hipSetDevice(h->device));
+    int rc = ensure(h, h->train_delta, h->train_delta_cap, m * classes);
+    if (rc) return rc;
+    TrainCtx ctx{h, m, n, in_dim, classes, (in_dim + 1) * classes, X, y, perm_in, W, velocity,
+                 grads_out, loss_out, lr, momentum};
+    // a chunk is a whole number of step pairs: about one block's worth of pairs, at least one step pair
+    const int64_t step_pairs = std::max<int64_t>(1, 32 / m);
+    return balance_epoch_impl(h, m, n, ctx.d, nullptr, train_generate, &ctx, step_pairs * m, perm_in,
+                              signs_out, perm_out, nullptr, nullptr, nullptr);
 }
 
 int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,

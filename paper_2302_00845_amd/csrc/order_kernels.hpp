@@ -151,4 +151,99 @@ __global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *
     }
 }
 
+// ---------------------------------------------------------------------------
+// One optimisation step of the m simulated workers ("CD-GraB Workers" lines 4-7
+// with the server's average, "CD-GraB Parameter Server" lines 5-7), for the
+// softmax-regression model.  Step j: worker i takes example perm[i][j].
+//
+// train_step_delta: one wavefront per worker computes delta_i = softmax(W^T [x;1]) - onehot(y)
+// at the current weights, and the example's loss.
+__global__ __launch_bounds__(kGradWaves * 64) void train_step_delta(const float *__restrict__ X,
+                                                                    const int32_t *__restrict__ y,
+                                                                    const int32_t *__restrict__ perm,
+                                                                    const float *__restrict__ W,
+                                                                    float *__restrict__ delta_out,
+                                                                    float *__restrict__ loss_out, int64_t m,
+                                                                    int64_t n, int64_t j, int in_dim,
+                                                                    int classes)
+{
+    extern __shared__ float dyn[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int per_wave = in_dim + 1 + classes;
+    float *xs = dyn + wave * per_wave;
+    float *logit = xs + in_dim + 1;
+    const int64_t i = (int64_t)blockIdx.x * kGradWaves + wave;
+    const bool active = i < m;
+    int64_t id = 0;
+    if (active) {
+        id = perm ? (int64_t)perm[i * n + j] : j;
+        const float *x = X + (i * n + id) * in_dim;
+        for (int r = lane; r < in_dim; r += 64) xs[r] = x[r];
+        if (lane == 0) xs[in_dim] = 1.0f;
+    }
+    __syncthreads();
+    float mx = -INFINITY;
+    if (active) {
+        for (int c = 0; c < classes; ++c) {
+            float part = 0.f;
+            for (int r = lane; r <= in_dim; r += 64) part = fmaf(xs[r], W[(int64_t)r * classes + c], part);
+            float z = wave_sum(part);
+            if (lane == 0) logit[c] = z;
+            mx = fmaxf(mx, z);
+        }
+    }
+    __syncthreads();
+    if (active) {
+        float Z = 0.f;
+        for (int c = lane; c < classes; c += 64) Z += expf(logit[c] - mx);
+        Z = wave_sum(Z);
+        const int label = y[i * n + id];
+        for (int c = lane; c < classes; c += 64) {
+            float p = expf(logit[c] - mx) / Z;
+            delta_out[i * classes + c] = p - (c == label ? 1.0f : 0.0f);
+            if (c == label && loss_out) loss_out[i * n + j] = -(logit[c] - mx - logf(Z));
+        }
+    }
+}
+
+// train_step_update: one thread per parameter p = (r, c).  Writes every worker's
+// gradient row of this step into the staging chunk (pair-major: pair (k, i) of the
+// chunk holds rows [2q], [2q+1] with q = (k - k_first) m + i) and optionally into
+// grads_out[m][n][d], forms the average gradient and applies SGD with momentum
+// (v <- momentum v + gbar; w <- w - lr v).
+__global__ __launch_bounds__(256) void train_step_update(const float *__restrict__ X,
+                                                         const int32_t *__restrict__ perm,
+                                                         const float *__restrict__ delta,
+                                                         float *__restrict__ W, float *__restrict__ velocity,
+                                                         float *__restrict__ staging,
+                                                         float *__restrict__ grads_out, int64_t m, int64_t n,
+                                                         int64_t j, int64_t k_first, int in_dim, int classes,
+                                                         float lr, float momentum)
+{
+    const int64_t d = (int64_t)(in_dim + 1) * classes;
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= d) return;
+    const int r = (int)(p / classes);
+    const int c = (int)(p - (int64_t)r * classes);
+    const int64_t k = j >> 1;
+    const int which = (int)(j & 1);
+    float sum = 0.f;
+    for (int64_t i = 0; i < m; ++i) {
+        const int64_t id = perm ? (int64_t)perm[i * n + j] : j;
+        const float xr = (r < in_dim) ? X[(i * n + id) * in_dim + r] : 1.0f;
+        const float g = xr * delta[i * classes + c];
+        const int64_t q = (k - k_first) * m + i;
+        staging[(2 * q + which) * d + p] = g;
+        if (grads_out) grads_out[(i * n + j) * d + p] = g;
+        sum += g;
+    }
+    const float gbar = sum / (float)m;
+    float step = gbar;
+    if (velocity) {
+        step = momentum * velocity[p] + gbar;
+        velocity[p] = step;
+    }
+    W[p] = W[p] - lr * step;
+}
+
 }  // namespace cdgrab

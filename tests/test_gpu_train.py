@@ -1,0 +1,111 @@
+"""GPU tests of cdgrab_train_epoch_softmax: the workers' gradients at the evolving
+weights, the server's average and the SGD(+momentum) update against the double
+oracle, and the balancing of the epoch's rows against the oracle walking the same
+bytes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from parity import check_epoch, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2302_00845_amd as p
+    return p
+
+
+def problem(seed, m, n, in_dim, classes, scale=10.0):
+    X, y, W = workloads.softmax_problem(seed, m * n, in_dim, classes)
+    return X.reshape(m, n, in_dim), y.reshape(m, n), (W * scale).astype(np.float32)
+
+
+@pytest.mark.parametrize("m,n,in_dim,classes,momentum", [
+    (4, 16, 12, 3, 0.0), (4, 16, 12, 3, 0.9), (16, 12, 40, 10, 0.9), (3, 10, 7, 5, 0.5),
+    (40, 6, 9, 4, 0.9), (1, 8, 5, 2, 0.0), (32, 4, 784, 10, 0.9),
+])
+def test_epoch_matches_oracle(lib, m, n, in_dim, classes, momentum):
+    X, y, W0 = problem(m + n, m, n, in_dim, classes)
+    perm = workloads.random_perms(3, m, n)
+    lr = 0.2
+    h = lib.Handle()
+    W = torch.from_numpy(W0.copy()).cuda()
+    v = torch.zeros(W.numel(), dtype=torch.float32, device="cuda") if momentum else None
+    out = lib.cdgrab_train_epoch_softmax(h, torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(), W,
+                                         perm_in=torch.from_numpy(perm).cuda(), velocity=v, lr=lr,
+                                         momentum=momentum, want_grads=True, want_loss=True)
+    torch.cuda.synchronize()
+    ref = oracle.train_epoch_softmax(X, y, perm, W0, None, lr, momentum)
+    rows = out["grads"].cpu().numpy()
+    # fp32 model arithmetic against the double oracle: per-step rounding ~1e-7 relative,
+    # n steps of a contractive update -> well inside 1e-5 / 1e-4 at these sizes
+    assert rel_l2(W.cpu().numpy(), ref["W"]) <= 1e-5
+    if momentum:
+        assert rel_l2(v.cpu().numpy(), ref["v"]) <= 1e-4
+    for j in range(n):
+        assert rel_l2(rows[:, j], ref["rows"][:, j]) <= 1e-4, j
+    np.testing.assert_allclose(out["loss"].cpu().numpy(), ref["loss"], rtol=1e-4, atol=1e-6)
+    # balancing: judged on the bytes the GPU balanced
+    got = {"signs": out["signs"].cpu().numpy(), "perm": out["perm"].cpu().numpy()}
+    check_epoch(rows, got, perm)
+    # and it equals the dense entry point on the same rows, bit for bit
+    dense = lib.cdgrab_balance_epoch(h, m, n, rows.shape[2], grads=out["grads"],
+                                     perm_in=torch.from_numpy(perm).cuda())
+    assert torch.equal(dense["signs"], out["signs"]) and torch.equal(dense["perm"], out["perm"])
+
+
+def test_weights_really_evolve_inside_the_epoch(lib):
+    """With lr = 0 every row is the gradient at W0; with lr > 0 later rows differ."""
+    m, n, in_dim, classes = 4, 8, 10, 3
+    X, y, W0 = problem(1, m, n, in_dim, classes)
+    h = lib.Handle()
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    W = torch.from_numpy(W0.copy()).cuda()
+    frozen = lib.cdgrab_train_epoch_softmax(h, Xd, yd, W, lr=0.0, want_grads=True)["grads"].cpu().numpy()
+    assert np.array_equal(W.cpu().numpy(), W0)
+    want = oracle.softmax_pergrad(X.reshape(m * n, in_dim), y.reshape(-1), W0).reshape(m, n, -1)
+    assert rel_l2(frozen, want) <= 1e-5
+    moving = lib.cdgrab_train_epoch_softmax(h, Xd, yd, W, lr=0.5, want_grads=True)["grads"].cpu().numpy()
+    assert np.array_equal(moving[:, 0], frozen[:, 0])
+    assert np.abs(moving[:, n - 1] - frozen[:, n - 1]).max() > 1e-3
+
+
+def test_multi_epoch_training_lowers_loss(lib):
+    """A few epochs with the permutations carried over (the T-epoch loop of Sec. 3.3)."""
+    m, n, in_dim, classes = 16, 64, 32, 10
+    rng = np.random.default_rng(0)
+    Wtrue = rng.standard_normal((in_dim + 1, classes))
+    X = rng.random((m, n, in_dim), dtype=np.float32)
+    logits = np.concatenate([X, np.ones((m, n, 1), np.float32)], -1) @ Wtrue * 4
+    y = logits.argmax(-1).astype(np.int32)
+    h = lib.Handle()
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    W = torch.zeros((in_dim + 1, classes), dtype=torch.float32, device="cuda")
+    v = torch.zeros(W.numel(), dtype=torch.float32, device="cuda")
+    perm = torch.from_numpy(workloads.random_perms(0, m, n)).cuda()
+    losses = []
+    for epoch in range(6):
+        out = lib.cdgrab_train_epoch_softmax(h, Xd, yd, W, perm_in=perm, velocity=v, lr=0.5, momentum=0.9)
+        perm = out["perm"]
+        losses.append(float(out["loss"].mean()))
+        p = perm.cpu().numpy()
+        assert all(np.array_equal(np.sort(p[i]), np.arange(n)) for i in range(m))
+    print("epoch losses", ["%.4f" % l for l in losses])
+    assert losses[-1] < 0.6 * losses[0]
+
+
+def test_argument_errors(lib):
+    h = lib.Handle()
+    X = torch.zeros((2, 3, 4), dtype=torch.float32, device="cuda")
+    y = torch.zeros((2, 3), dtype=torch.int32, device="cuda")
+    W = torch.zeros((5, 3), dtype=torch.float32, device="cuda")
+    with pytest.raises(lib.CdgrabError):
+        lib.cdgrab_train_epoch_softmax(h, X, y, W)                      # odd n
+    X = torch.zeros((2, 4, 4), dtype=torch.float32, device="cuda")
+    y = torch.zeros((2, 4), dtype=torch.int32, device="cuda")
+    with pytest.raises(lib.CdgrabError):
+        lib.cdgrab_train_epoch_softmax(h, X, y, W, momentum=0.9)        # momentum without velocity

@@ -372,3 +372,45 @@ def test_pergrad_rejects_bad_label():
     y[1] = 3
     with pytest.raises(ValueError):
         oracle.softmax_pergrad(X, y, W)
+
+
+# --------------------------------------------------------------------------- training epoch
+def test_train_epoch_against_autograd_sgd():
+    """The oracle's training epoch (workers' gradient at the current weights, server
+    average, SGD with momentum) against torch autograd + torch.optim.SGD in double,
+    a library routine with the same update rule (v <- mu v + g; w <- w - lr v)."""
+    import torch
+    m, n, in_dim, classes = 3, 6, 5, 4
+    X, y, W = workloads.softmax_problem(4, m * n, in_dim, classes)
+    X, y = X.reshape(m, n, in_dim), y.reshape(m, n)
+    perm = workloads.random_perms(5, m, n)
+    out = oracle.train_epoch_softmax(X, y, perm, W * 10, None, lr=0.3, momentum=0.9)
+    Wt = torch.tensor(W * 10, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([Wt], lr=0.3, momentum=0.9)
+    rows = np.zeros((m, n, (in_dim + 1) * classes))
+    losses = np.zeros((m, n))
+    for j in range(n):
+        opt.zero_grad()
+        total = 0
+        per = []
+        for i in range(m):
+            e = perm[i, j]
+            xe = torch.cat([torch.tensor(X[i, e], dtype=torch.float64), torch.ones(1, dtype=torch.float64)])
+            li = torch.nn.functional.cross_entropy((xe @ Wt)[None], torch.tensor([int(y[i, e])]))
+            gi, = torch.autograd.grad(li, Wt, retain_graph=True)
+            rows[i, j] = gi.numpy().reshape(-1)
+            losses[i, j] = li.item()
+            per.append(li)
+        (sum(per) / m).backward()
+        opt.step()
+    np.testing.assert_allclose(out["W"], Wt.detach().numpy(), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(out["rows"], rows, rtol=2e-6, atol=1e-9)       # rows are rounded to fp32
+    np.testing.assert_allclose(out["loss"], losses, rtol=1e-12)
+    # a stale-weights mistake would be visible: the last step's rows differ from those at W0
+    stale = oracle.softmax_pergrad(X.reshape(m * n, in_dim), y.reshape(-1), (W * 10).astype(np.float32))
+    stale = stale.reshape(m, n, -1)
+    last = np.stack([stale[i, perm[i, n - 1]] for i in range(m)])
+    assert np.abs(last - out["rows"][:, n - 1]).max() > 1e-3
+    # the balancing attached to the epoch is the plain server walk on those rows
+    ref = oracle.server_epoch(out["rows"], perm)
+    assert np.array_equal(ref["eps"], out["eps"]) and np.array_equal(ref["perm"], out["perm"])
