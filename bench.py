@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--no-input-drain", action="store_true",
                     help="do not let the input generator drain its written rows out of the last-level "
                          "cache before the balancer's timed region")
+    ap.add_argument("--skip-undrained-step", action="store_true",
+                    help="do not run the extra epoch that measures the balancer without the input drain")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (a kernel of known HBM traffic, to scale "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
@@ -186,7 +188,7 @@ def main():
 
     # the same epoch without the generator's cache drain (its write-back then lands in pass 1)
     undrained = None
-    if w.kind == "stream" and not args.no_input_drain:
+    if w.kind == "stream" and not args.no_input_drain and not args.skip_undrained_step:
         synth.set_input_drain(False, str(dev))
         _, tu = step()
         synth.set_input_drain(True, str(dev))

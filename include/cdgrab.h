@@ -149,6 +149,15 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                          int32_t *perm_out, float *r_out, double *r64_out,
                          double *dots_out);
 
+/* The uncoordinated ablation baseline "ID-GraB (PairBal)" (Sec. 5, ablation study):
+ * every worker balances its own pairs on its own running sum, with no shared state,
+ * i.e. m separate runs of cdgrab_balance_epoch with m = 1.  Same layouts as there:
+ *   grads [m][n][d] fp32 dev, perm_in [m][n] or NULL, signs_out [m][n/2], perm_out [m][n].
+ * Errors: as cdgrab_balance_epoch. */
+int cdgrab_balance_epoch_independent(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
+                                     const float *grads, const int32_t *perm_in,
+                                     int8_t *signs_out, int32_t *perm_out);
+
 /* One training epoch of the softmax-regression model under CD-GraB ("CD-GraB
  * Workers" + "CD-GraB Parameter Server", Sec. 3.3), the m workers simulated on one
  * GPU.  For step j = 0 .. n-1: worker i computes the gradient of example

@@ -8,6 +8,7 @@ from .cdgrab import (  # noqa: F401
     CdgrabError,
     Handle,
     cdgrab_balance_epoch,
+    cdgrab_balance_epoch_independent,
     cdgrab_herding_bound,
     cdgrab_pergrad,
     cdgrab_plan_epoch,

@@ -86,6 +86,8 @@ def load_library():
     lib.cdgrab_balance_epoch.restype = ctypes.c_int
     lib.cdgrab_reorder.argtypes = [P, i64, i64, P, P, P]
     lib.cdgrab_reorder.restype = ctypes.c_int
+    lib.cdgrab_balance_epoch_independent.argtypes = [P, i64, i64, i64, P, P, P, P]
+    lib.cdgrab_balance_epoch_independent.restype = ctypes.c_int
     lib.cdgrab_train_epoch_softmax.argtypes = [P, i64, i64, i64, i64, P, P, P, P, P, ctypes.c_float,
                                                ctypes.c_float, P, P, P, P]
     lib.cdgrab_train_epoch_softmax.restype = ctypes.c_int
@@ -255,3 +257,15 @@ def cdgrab_train_epoch_softmax(h: Handle, X: torch.Tensor, y: torch.Tensor, W: t
         grads.data_ptr() if grads is not None else None,
         loss.data_ptr() if loss is not None else None))
     return {"signs": signs, "perm": perm, "grads": grads, "loss": loss}
+
+
+def cdgrab_balance_epoch_independent(h: Handle, grads: torch.Tensor,
+                                     perm_in: Optional[torch.Tensor] = None) -> dict:
+    """ID-GraB (PairBal): m independent one-worker walks over grads[m][n][d]."""
+    m, n, d = grads.shape
+    signs = torch.empty((m, n // 2), dtype=torch.int8, device=h.device)
+    perm = torch.empty((m, n), dtype=torch.int32, device=h.device)
+    h._check(h._lib.cdgrab_balance_epoch_independent(
+        h._h, m, n, d, _ptr(grads, torch.float32, (m, n, d), "grads", h.device),
+        _ptr(perm_in, torch.int32, (m, n), "perm_in", h.device), signs.data_ptr(), perm.data_ptr()))
+    return {"signs": signs, "perm": perm}

@@ -383,7 +383,7 @@ __global__ __launch_bounds__(kThreads) void pass2_apply(RowMap rm, const int8_t 
 // partial sums are added in wave order through LDS, and 256 threads update one
 // element each.  Four times the workgroups and a quarter of the loads per thread
 // of the flat form, which is what a latency-bound launch needs.
-template <int BB, int VW>
+template <int BB, int VW, bool FULL>
 __global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const int8_t *__restrict__ eps_blk,
                                                               double *__restrict__ r_sum)
 {
@@ -391,30 +391,37 @@ __global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const i
     const int64_t d = rm.d;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t e = (int64_t)blockIdx.x * 256 + lane * 4;
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    const int64_t mine = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    // this thread's running-sum element is requested first so that its latency
+    // overlaps the row loads
+    const double r_old = (mine < d) ? r_sum[mine] : 0.0;
     constexpr int PER = BB / kWaves;
+    float4 a[PER], b[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
         const int j = wave * PER + q;
-        if (j < rm.nb) {
-            float4 a = load4<VW>(rm.row(j, 0), e, d);
-            float4 b = load4<VW>(rm.row(j, 1), e, d);
-            double sg = (double)eps_blk[j];
-            acc[0] = __builtin_fma(sg, (double)b.x - (double)a.x, acc[0]);
-            acc[1] = __builtin_fma(sg, (double)b.y - (double)a.y, acc[1]);
-            acc[2] = __builtin_fma(sg, (double)b.z - (double)a.z, acc[2]);
-            acc[3] = __builtin_fma(sg, (double)b.w - (double)a.w, acc[3]);
-        }
+        const bool have = FULL || j < rm.nb;
+        a[q] = load4<VW>(have ? rm.row(j, 0) : nullptr, e, d);
+        b[q] = load4<VW>(have ? rm.row(j, 1) : nullptr, e, d);
+    }
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int j = wave * PER + q;
+        const double sg = (FULL || j < rm.nb) ? (double)eps_blk[j] : 0.0;
+        acc[0] = __builtin_fma(sg, (double)b[q].x - (double)a[q].x, acc[0]);
+        acc[1] = __builtin_fma(sg, (double)b[q].y - (double)a[q].y, acc[1]);
+        acc[2] = __builtin_fma(sg, (double)b[q].z - (double)a[q].z, acc[2]);
+        acc[3] = __builtin_fma(sg, (double)b[q].w - (double)a[q].w, acc[3]);
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) part[wave][lane * 4 + q] = acc[q];
     __syncthreads();
-    const int64_t mine = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (mine < d) {
         double sum = 0.0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) sum += part[w][threadIdx.x];
-        r_sum[mine] += sum;
+        r_sum[mine] = r_old + sum;
     }
 }
 

@@ -169,8 +169,13 @@ template <int BB, int VW>
 void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
     // short rows: too few flat workgroups to hide latency -> split the pairs over waves
     if (groups < 2 * h->num_cu) {
-        hipLaunchKernelGGL((pass2_apply_split<BB, VW>), dim3((unsigned)((rm.d + 255) / 256)), dim3(kThreads),
-                           0, h->stream, rm, h->eps_blk, h->r_sum);
+        const dim3 grid((unsigned)((rm.d + 255) / 256));
+        if (rm.nb == BB)
+            hipLaunchKernelGGL((pass2_apply_split<BB, VW, true>), grid, dim3(kThreads), 0, h->stream, rm,
+                               h->eps_blk, h->r_sum);
+        else
+            hipLaunchKernelGGL((pass2_apply_split<BB, VW, false>), grid, dim3(kThreads), 0, h->stream, rm,
+                               h->eps_blk, h->r_sum);
         return;
     }
     if (rm.nb == BB)
@@ -390,6 +395,23 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
                          double *dots_out) {
     return balance_epoch_impl(h, m, n, d, grads, gen, gen_ctx, 0, perm_in, signs_out, perm_out, r_out,
                               r64_out, dots_out);
+}
+
+int cdgrab_balance_epoch_independent(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
+                                     const float *grads, const int32_t *perm_in, int8_t *signs_out,
+                                     int32_t *perm_out) {
+    if (!h) return CDGRAB_EINVAL;
+    if (m < 1) return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_independent: need m>=1");
+    if (!grads || !signs_out || !perm_out)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_independent: null pointer");
+    // m separate one-worker walks: worker i balances its own n/2 pairs on its own running sum
+    for (int64_t i = 0; i < m; ++i) {
+        int rc = balance_epoch_impl(h, 1, n, d, grads + i * n * d, nullptr, nullptr, 0,
+                                    perm_in ? perm_in + i * n : nullptr, signs_out + i * (n / 2),
+                                    perm_out + i * n, nullptr, nullptr, nullptr);
+        if (rc) return rc;
+    }
+    return CDGRAB_OK;
 }
 
 namespace {

@@ -45,6 +45,46 @@ def test_matches_oracle(lib, m, n, d, with_perm):
     assert abs(got - want) <= 1e-9 * max(want, 1e-30)
 
 
+def test_independent_walks_match_oracle(lib):
+    """ID-GraB (PairBal): worker i's signs and order are those of a one-worker walk."""
+    m, n, d = 5, 24, 300
+    z = workloads.heavy_rows(9, m, n, d)
+    perm_in = workloads.random_perms(4, m, n)
+    h = lib.Handle()
+    out = lib.cdgrab_balance_epoch_independent(h, torch.from_numpy(z).cuda(), torch.from_numpy(perm_in).cuda())
+    signs, perm = out["signs"].cpu().numpy(), out["perm"].cpu().numpy()
+    for i in range(m):
+        ref = oracle.server_epoch(z[i:i + 1], perm_in[i:i + 1])
+        assert np.array_equal(ref["eps"][0], signs[i]) and np.array_equal(ref["perm"][0], perm[i])
+
+
+def _run_orders(lib, h, z, epochs, coordinated):
+    m, n, d = z.shape
+    perm = torch.arange(n, dtype=torch.int32, device="cuda").repeat(m, 1).contiguous()
+    for _ in range(epochs):
+        idx = perm.long().unsqueeze(-1).expand(m, n, d)
+        visited = torch.gather(z, 1, idx).contiguous()
+        if coordinated:
+            perm = lib.cdgrab_balance_epoch(h, m, n, d, grads=visited, perm_in=perm, want_r32=False)["perm"]
+        else:
+            perm = lib.cdgrab_balance_epoch_independent(h, visited, perm)["perm"]
+    return perm
+
+
+def test_coordination_matters_with_many_workers(lib):
+    """The ablation's point (Sec. 5 and App. E): with many workers, independent
+    balancing loses to coordinated balancing on the parallel herding objective."""
+    h = lib.Handle()
+    N, d, m = 1 << 15, 16, 64
+    vec = workloads.herding_vectors(5, N, d)
+    z = torch.from_numpy(vec.reshape(m, N // m, d)).cuda()
+    coord = gpu_bound(lib, h, z, _run_orders(lib, h, z, 8, True))
+    indep = gpu_bound(lib, h, z, _run_orders(lib, h, z, 8, False))
+    rand = np.mean([gpu_bound(lib, h, z, workloads.random_perms(s, m, N // m)) for s in range(3)])
+    print("m=%d coordinated %.2f independent %.2f random %.2f" % (m, coord, indep, rand))
+    assert coord < 0.5 * indep and indep < rand
+
+
 def test_synthetic_herding_study_reduced(lib):
     """App. E's synthetic study, scaled down (2^16 unit vectors in 16 dimensions
     instead of 10^6): CD-GraB's orders reach a parallel herding bound far below that
