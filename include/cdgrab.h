@@ -37,7 +37,7 @@ typedef struct cdgrab_handle cdgrab_handle;
 
 typedef struct cdgrab_options {
     int32_t device;      /* HIP device ordinal                                        */
-    int32_t block_pairs; /* Bb: pairs resolved per HBM pass; 0 = choose, else 16 or 32 */
+    int32_t block_pairs; /* Bb: pairs resolved per HBM pass; 0 = choose, else 16, 32 or 64 */
     void *stream;        /* hipStream_t to enqueue on; NULL = the null stream         */
     int32_t timing;      /* 0 off; 1 record events around generator / balancer work;
                             2 additionally around every balancer kernel               */

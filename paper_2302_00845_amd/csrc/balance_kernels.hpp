@@ -28,9 +28,12 @@ typedef double double4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
 
-// Where the rows of the current block live.  Flattened pair p = p0 + j belongs to
-// worker p % m and is that worker's pair p / m; the host passes p0 already split as
-// (k0, i0) = (p0 / m, p0 % m).  Dense input is [m][n][d]; a staging block is [Bb][2][d].
+// Where the rows of the current block live: element offsets from `base` of the
+// first and second row of each pair, filled in by the host (dense input [m][n][d]:
+// flattened pair p belongs to worker p % m and is its pair p / m; a staging block
+// is [Bb][2][d]).  Passed by value: uniform indices become scalar loads.
+constexpr int kMaxBlockPairs = 64;
+
 struct RowMap {
     const float *base;
     int64_t d;
@@ -38,18 +41,11 @@ struct RowMap {
     int64_t k0;     // pair index (per worker) of the block's first flattened pair
     int32_t i0;     // worker of the block's first flattened pair
     int32_t m;
-    int32_t dense;  // 1: base is the caller's [m][n][d] array; 0: base is a staging block
     int32_t nb;     // valid pairs in this block (<= Bb)
+    int32_t pad_;
+    int64_t off[2 * kMaxBlockPairs];  // off[2 j + which]
 
-    __device__ __forceinline__ const float *row(int j, int which) const {
-        if (dense) {
-            uint32_t q = (uint32_t)(i0 + j);
-            uint32_t dk = q / (uint32_t)m;
-            uint32_t i = q - dk * (uint32_t)m;
-            return base + (((int64_t)i * n) + 2 * (k0 + dk) + which) * d;
-        }
-        return base + (int64_t)(2 * j + which) * d;
-    }
+    __device__ __forceinline__ const float *row(int j, int which) const { return base + off[2 * j + which]; }
 };
 
 // Four consecutive fp32 elements starting at element e of a row, zero beyond d or
@@ -304,14 +300,12 @@ __global__ __launch_bounds__(kThreads) void resolve_signs(const double *__restri
         int tile = idx >> 8, v = (idx >> 6) & 3, ln = idx & 63;
         int i, j;
         mfma_f64_16x16_coord(ln, v, i, j);
-        if (L::RG == 1) {
-            G[i][j] = val;
-        } else {
-            // tiles in order (0,0), (0,1), (1,1)
-            if (tile == 0) G[i][j] = val;
-            else if (tile == 1) { G[i][16 + j] = val; G[16 + j][i] = val; }
-            else G[16 + i][16 + j] = val;
-        }
+        // tiles are stored row group by row group, upper triangle only: (0,0), (0,1), .., (1,1), ..
+        int tg = 0, th = tile;
+        while (th >= L::RG - tg) { th -= L::RG - tg; ++tg; }
+        th += tg;
+        G[16 * tg + i][16 * th + j] = val;
+        if (th != tg) G[16 * th + j][16 * tg + i] = val;
     }
     __syncthreads();
     if (threadIdx.x >= 64) return;
@@ -378,28 +372,30 @@ __global__ __launch_bounds__(kThreads) void pass2_apply(RowMap rm, const int8_t 
 }
 
 // ---------------------------------------------------------------------------
-// Pass 2 for short rows: the block's pairs are split over the four waves of a
-// workgroup (each wave sums BB/4 pairs for 256 consecutive elements), the four
-// partial sums are added in wave order through LDS, and 256 threads update one
-// element each.  Four times the workgroups and a quarter of the loads per thread
-// of the flat form, which is what a latency-bound launch needs.
+// Pass 2 for short rows: a workgroup owns 64 consecutive elements; its 256 threads
+// are 16 element-quads x 16 pair groups, each thread sums BB/16 pairs for its quad,
+// the 16 partial sums are added in group order through LDS, and 64 threads update
+// one element each.  Sixteen times the workgroups and a sixteenth of the loads per
+// thread of the flat form, which is what a latency-bound launch needs.
+constexpr int kSplitGroups = 16;
+constexpr int kSplitElems = (kThreads / kSplitGroups) * 4;  // 64 elements per workgroup
+
 template <int BB, int VW, bool FULL>
 __global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const int8_t *__restrict__ eps_blk,
                                                               double *__restrict__ r_sum)
 {
-    __shared__ double part[kWaves][256];
+    __shared__ double part[kSplitGroups][kSplitElems];
     const int64_t d = rm.d;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t e = (int64_t)blockIdx.x * 256 + lane * 4;
-    const int64_t mine = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    // this thread's running-sum element is requested first so that its latency
-    // overlaps the row loads
-    const double r_old = (mine < d) ? r_sum[mine] : 0.0;
-    constexpr int PER = BB / kWaves;
+    const int quad = threadIdx.x % (kThreads / kSplitGroups), grp = threadIdx.x / (kThreads / kSplitGroups);
+    const int64_t e = (int64_t)blockIdx.x * kSplitElems + quad * 4;
+    const int64_t mine = (int64_t)blockIdx.x * kSplitElems + threadIdx.x;
+    // the running-sum element is requested first so that its latency overlaps the row loads
+    const double r_old = (threadIdx.x < kSplitElems && mine < d) ? r_sum[mine] : 0.0;
+    constexpr int PER = BB / kSplitGroups;
     float4 a[PER], b[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-        const int j = wave * PER + q;
+        const int j = grp * PER + q;
         const bool have = FULL || j < rm.nb;
         a[q] = load4<VW>(have ? rm.row(j, 0) : nullptr, e, d);
         b[q] = load4<VW>(have ? rm.row(j, 1) : nullptr, e, d);
@@ -407,7 +403,7 @@ __global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const i
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-        const int j = wave * PER + q;
+        const int j = grp * PER + q;
         const double sg = (FULL || j < rm.nb) ? (double)eps_blk[j] : 0.0;
         acc[0] = __builtin_fma(sg, (double)b[q].x - (double)a[q].x, acc[0]);
         acc[1] = __builtin_fma(sg, (double)b[q].y - (double)a[q].y, acc[1]);
@@ -415,12 +411,12 @@ __global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const i
         acc[3] = __builtin_fma(sg, (double)b[q].w - (double)a[q].w, acc[3]);
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) part[wave][lane * 4 + q] = acc[q];
+    for (int q = 0; q < 4; ++q) part[grp][quad * 4 + q] = acc[q];
     __syncthreads();
-    if (mine < d) {
+    if (threadIdx.x < kSplitElems && mine < d) {
         double sum = 0.0;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) sum += part[w][threadIdx.x];
+        for (int g = 0; g < kSplitGroups; ++g) sum += part[g][threadIdx.x];
         r_sum[mine] = r_old + sum;
     }
 }

@@ -43,8 +43,8 @@ struct cdgrab_handle {
 
     double *r_sum = nullptr;   int64_t r_cap = 0;         // doubles
     double *partials = nullptr; int64_t partials_cap = 0; // doubles
-    double *reduced = nullptr;                            // kReduceSlices x PartLayout<32>::PART doubles
-    int8_t *eps_blk = nullptr;                            // 32 signs
+    double *reduced = nullptr;                            // kReduceSlices x PartLayout<64>::PART doubles
+    int8_t *eps_blk = nullptr;                            // up to 64 signs of the current block
     int32_t *flag = nullptr;                              // reorder's bad-sign flag
     float *train_delta = nullptr; int64_t train_delta_cap = 0;  // [m][classes] softmax deltas of one step
     double *herd_ws = nullptr; int64_t herd_cap = 0;      // herding evaluator: segment sums, starts, mean
@@ -84,21 +84,27 @@ int pick_vector_width(int64_t d, int64_t base_align) {
     return 1;
 }
 
-int pick_block_pairs(int64_t pairs, int32_t requested) {
-    if (requested == 16 || requested == 32) return requested;
-    return pairs > 16 ? 32 : 16;
+// 32 pairs per block keep the double-precision Gram tiles under the HBM time for
+// long rows; short rows are bound by launches, not bytes, and take 64.
+int pick_block_pairs(int64_t pairs, int64_t d, int32_t requested) {
+    if (requested == 16 || requested == 32 || requested == 64) return requested;
+    if (pairs <= 16) return 16;
+    if (pairs > 32 && d <= 65536) return 64;
+    return 32;
 }
 
-int part_size(int bb) { return bb == 32 ? PartLayout<32>::PART : PartLayout<16>::PART; }
+int part_size(int bb) {
+    return bb == 64 ? PartLayout<64>::PART : bb == 32 ? PartLayout<32>::PART : PartLayout<16>::PART;
+}
 
 int plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs, int32_t streamed,
                int64_t base_align, int num_cu, int32_t pass1_groups_opt, cdgrab_plan *plan) {
     if (m < 1 || n < 2 || (n & 1) || d < 1 || !plan) return CDGRAB_EINVAL;
-    if (block_pairs != 0 && block_pairs != 16 && block_pairs != 32) return CDGRAB_EINVAL;
+    if (block_pairs != 0 && block_pairs != 16 && block_pairs != 32 && block_pairs != 64) return CDGRAB_EINVAL;
     if (base_align < 4 || (base_align & (base_align - 1))) return CDGRAB_EINVAL;
     if (m > (INT64_MAX / n) / d || m > (1 << 30)) return CDGRAB_EINVAL;
     plan->pairs = m * (n / 2);
-    plan->block_pairs = pick_block_pairs(plan->pairs, block_pairs);
+    plan->block_pairs = pick_block_pairs(plan->pairs, d, block_pairs);
     plan->blocks = (plan->pairs + plan->block_pairs - 1) / plan->block_pairs;
     plan->vector_width = pick_vector_width(d, streamed ? 256 : base_align);
     // long rows stream through 128-element tiles with two resident workgroups per CU;
@@ -167,9 +173,9 @@ void launch_pass1(cdgrab_handle *h, const RowMap &rm, const cdgrab_plan &plan) {
 }
 template <int BB, int VW>
 void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
-    // short rows: too few flat workgroups to hide latency -> split the pairs over waves
+    // short rows: too few flat workgroups to hide latency -> split the pairs over thread groups
     if (groups < 2 * h->num_cu) {
-        const dim3 grid((unsigned)((rm.d + 255) / 256));
+        const dim3 grid((unsigned)((rm.d + kSplitElems - 1) / kSplitElems));
         if (rm.nb == BB)
             hipLaunchKernelGGL((pass2_apply_split<BB, VW, true>), grid, dim3(kThreads), 0, h->stream, rm,
                                h->eps_blk, h->r_sum);
@@ -226,8 +232,8 @@ int cdgrab_create(cdgrab_handle **out, const cdgrab_options *opt) {
     *out = nullptr;
     cdgrab_options o{};
     if (opt) o = *opt;
-    if (o.block_pairs != 0 && o.block_pairs != 16 && o.block_pairs != 32)
-        return fail(nullptr, CDGRAB_EINVAL, "block_pairs must be 0, 16 or 32 (got %d)", o.block_pairs);
+    if (o.block_pairs != 0 && o.block_pairs != 16 && o.block_pairs != 32 && o.block_pairs != 64)
+        return fail(nullptr, CDGRAB_EINVAL, "block_pairs must be 0, 16, 32 or 64 (got %d)", o.block_pairs);
     if (o.timing < 0 || o.timing > 2) return fail(nullptr, CDGRAB_EINVAL, "timing must be 0, 1 or 2");
     if (o.pass1_groups < 0 || o.pass1_groups > 65536)
         return fail(nullptr, CDGRAB_EINVAL, "pass1_groups out of range");
@@ -331,8 +337,8 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     if (rc) return rc;
     rc = ensure(h, h->partials, h->partials_cap, (int64_t)plan.pass1_groups * part_size(bb));
     if (rc) return rc;
-    if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)kReduceSlices * PartLayout<32>::PART); if (rc) return rc; }
-    if (!h->eps_blk) { fixed_cap = 0; rc = ensure(h, h->eps_blk, fixed_cap, (int64_t)32); if (rc) return rc; }
+    if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)kReduceSlices * PartLayout<64>::PART); if (rc) return rc; }
+    if (!h->eps_blk) { fixed_cap = 0; rc = ensure(h, h->eps_blk, fixed_cap, (int64_t)64); if (rc) return rc; }
     if (chunk_pairs <= 0) chunk_pairs = bb;
     if (streamed) { rc = ensure(h, h->staging, h->staging_cap, chunk_pairs * 2 * d); if (rc) return rc; }
 
@@ -344,9 +350,9 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                        h->stream, h->r_sum, h->r_cap);
 
     RowMap rm;
-    rm.d = d; rm.m = (int32_t)m; rm.n = n;
-    rm.dense = streamed ? 0 : 1;
+    rm.d = d; rm.m = (int32_t)m; rm.n = n; rm.pad_ = 0;
     rm.base = grads;
+    for (int64_t &o : rm.off) o = 0;
     const int64_t chunk = streamed ? chunk_pairs : plan.pairs;
     for (int64_t first = 0; first < plan.pairs; first += chunk) {
         const int64_t cnt = std::min<int64_t>(chunk, plan.pairs - first);
@@ -362,9 +368,19 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
             rm.i0 = (int32_t)(p0 - rm.k0 * m);
             rm.nb = (int32_t)std::min<int64_t>(bb, first + cnt - p0);
             if (streamed) rm.base = h->staging + (p0 - first) * 2 * d;
+            for (int j = 0; j < rm.nb; ++j) {
+                if (streamed) {
+                    rm.off[2 * j] = (int64_t)(2 * j) * d;
+                } else {
+                    const int64_t p = p0 + j, k = p / m, i = p - k * m;
+                    rm.off[2 * j] = (i * n + 2 * k) * d;
+                }
+                rm.off[2 * j + 1] = rm.off[2 * j] + d;
+            }
             MARK(h, 1, kBalance);
-            rc = (bb == 32) ? run_block_vw<32>(h, rm, plan, signs_out, dots_out)
-                            : run_block_vw<16>(h, rm, plan, signs_out, dots_out);
+            rc = (bb == 64)   ? run_block_vw<64>(h, rm, plan, signs_out, dots_out)
+                 : (bb == 32) ? run_block_vw<32>(h, rm, plan, signs_out, dots_out)
+                              : run_block_vw<16>(h, rm, plan, signs_out, dots_out);
             if (rc) return rc;
         }
     }
@@ -464,7 +480,7 @@ int cdgrab_train_epoch_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t i
     TrainCtx ctx{h, m, n, in_dim, classes, (in_dim + 1) * classes, X, y, perm_in, W, velocity,
                  grads_out, loss_out, lr, momentum};
     // a chunk is a whole number of step pairs: about one block's worth of pairs, at least one step pair
-    const int64_t step_pairs = std::max<int64_t>(1, 32 / m);
+    const int64_t step_pairs = std::max<int64_t>(1, 64 / m);
     return balance_epoch_impl(h, m, n, ctx.d, nullptr, train_generate, &ctx, step_pairs * m, perm_in,
                               signs_out, perm_out, nullptr, nullptr, nullptr);
 }

@@ -57,7 +57,7 @@ def test_plan_epoch_headline_shapes(p):
     assert c4["staging_bytes"] == 32 * 2 * 11_200_000 * 4
     assert c4["bytes_per_example"] == 8 * 11_200_000 + 12 * 11_200_000 / 32
     c2 = p.cdgrab_plan_epoch(16, 3750, 7850)
-    assert c2["pairs"] == 30000 and c2["blocks"] == 938 and c2["vector_width"] == 2
+    assert c2["pairs"] == 30000 and c2["block_pairs"] == 64 and c2["blocks"] == 469 and c2["vector_width"] == 2
     assert c2["staging_bytes"] == 0
     odd = p.cdgrab_plan_epoch(3, 4, 1001, base_align=4)
     assert odd["vector_width"] == 1 and odd["block_pairs"] == 16 and odd["blocks"] == 1

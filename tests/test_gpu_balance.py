@@ -35,7 +35,7 @@ def run_epoch(p, z, perm_in=None, block_pairs=0, pass1_groups=0):
 
 
 @pytest.mark.parametrize("case", HAND, ids=[c["name"] for c in HAND])
-@pytest.mark.parametrize("bb", [16, 32])
+@pytest.mark.parametrize("bb", [16, 32, 64])
 def test_hand_cases(lib, case, bb):
     got = run_epoch(lib, case["rows"], block_pairs=bb)
     assert got["signs"].tolist() == case["eps"].tolist()
@@ -43,11 +43,11 @@ def test_hand_cases(lib, case, bb):
     assert got["perm"].tolist() == case["perm"].tolist()
 
 
-@pytest.mark.parametrize("bb", [16, 32])
+@pytest.mark.parametrize("bb", [16, 32, 64])
 @pytest.mark.parametrize("seed,m,n,d,maxabs", [
     (0, 1, 2, 1, 3), (1, 1, 8, 3, 2), (2, 3, 6, 4, 2), (3, 4, 10, 7, 5), (4, 5, 4, 1, 1),
     (5, 2, 16, 2, 1), (6, 7, 12, 33, 9), (7, 4, 64, 1024, 8), (8, 3, 50, 777, 4),
-    (9, 16, 8, 130, 2), (10, 33, 6, 258, 3), (11, 2, 70, 4100, 8),
+    (9, 16, 8, 130, 2), (10, 33, 6, 258, 3), (11, 2, 70, 4100, 8), (12, 5, 60, 1500, 3),
 ])
 def test_exact_integer_inputs_bitwise(lib, bb, seed, m, n, d, maxabs):
     """Small-integer rows: all arithmetic is exact, so signs (ties included),
@@ -61,7 +61,7 @@ def test_exact_integer_inputs_bitwise(lib, bb, seed, m, n, d, maxabs):
     assert rep["dots_max_abs_err"] == 0.0
 
 
-@pytest.mark.parametrize("bb", [16, 32])
+@pytest.mark.parametrize("bb", [16, 32, 64])
 def test_config1_tiny_epoch(lib, bb):
     z = workloads.tiny_epoch(1234)                       # m=4, n=64, d=1024
     got = run_epoch(lib, z, block_pairs=bb)
