@@ -182,6 +182,11 @@ def main():
                     "avg_launch_ms": kernels[dom]["avg_launch_ms"],
                     "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"]}
         hp.close()
+    # practical ceiling: a plain streaming read of a buffer the size of one block's rows
+    read_ceiling = h.measure_read_bandwidth(int(min(max(8.0 * bb * d, 1 << 28), 3 << 30)))
+    if roofline is not None:
+        roofline["plain_read_GBs"] = read_ceiling
+        roofline["frac_of_plain_read"] = roofline["achieved"] / read_ceiling
     # whole balancer against the roofline: 8d + 12 d / Bb bytes per example
     bytes_per_example = 8.0 * d + 12.0 * d / bb
     balancer_gbs = bytes_per_example * N / (path_ms * 1e-3) / 1e9

@@ -149,6 +149,21 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                          int32_t *perm_out, float *r_out, double *r64_out,
                          double *dots_out);
 
+/* Centralized GraB balancing with a stale mean (Sec. 2.1: the prior method this
+ * paper builds on; run per worker it is the ablation's "ID-GraB (Bal)" with the
+ * deterministic rule).  One worker, n vectors (n may be odd):
+ *     z_j = g_j - stale_mean;   s_j = +1 if ||r + z_j|| < ||r - z_j|| else -1;   r += s_j z_j
+ *     perm_out = concat(L_pos, reverse(L_neg)) of perm_in under the signs s (Sec. 2.1)
+ *   grads [n][d] fp32 dev in visiting order, stale_mean [d] fp32 dev or NULL (zero),
+ *   perm_in [n] int32 dev or NULL, signs_out [n] int8 dev (s_j), perm_out [n] int32 dev,
+ *   mean_out [d] fp32 dev or NULL: mean of this epoch's vectors (next epoch's stale
+ *   mean; must not alias stale_mean), r64_out [d] fp64 dev or NULL: final running sum.
+ * Same arithmetic as cdgrab_balance_epoch.  Errors: EINVAL, ENOMEM, EHIP. */
+int cdgrab_balance_epoch_stale_mean(cdgrab_handle *h, int64_t n, int64_t d, const float *grads,
+                                    const float *stale_mean, const int32_t *perm_in,
+                                    int8_t *signs_out, int32_t *perm_out, float *mean_out,
+                                    double *r64_out);
+
 /* The uncoordinated ablation baseline "ID-GraB (PairBal)" (Sec. 5, ablation study):
  * every worker balances its own pairs on its own running sum, with no shared state,
  * i.e. m separate runs of cdgrab_balance_epoch with m = 1.  Same layouts as there:
@@ -198,6 +213,12 @@ int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,
  * Sums in double.  Errors: EINVAL (sizes, null), ENOMEM, EHIP. */
 int cdgrab_herding_bound(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *z,
                          const int32_t *perm, double *bound_out);
+
+/* Measurement aid, not part of the method: the HBM read bandwidth a plain streaming
+ * kernel (non-temporal 16-byte loads, no arithmetic) reaches on this device over a
+ * scratch buffer of `bytes` bytes, in GB/s (host double).  Allocates and frees the
+ * buffer, synchronises.  Errors: EINVAL (bytes outside 1 MiB .. 64 GiB), ENOMEM, EHIP. */
+int cdgrab_measure_read_bandwidth(cdgrab_handle *h, int64_t bytes, double *gb_per_s_out /*host*/);
 
 /* Timings of the last cdgrab_balance_epoch on this handle (options.timing >= 1).
  * Synchronises the stream.  Errors: EINVAL (timing was off), EHIP. */

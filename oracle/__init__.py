@@ -58,6 +58,8 @@ def _load():
     lib.oracle_parallel_herding.restype = dbl
     lib.oracle_train_epoch_softmax.argtypes = [i64, i64, i64, i64, P, P, P, P, P, dbl, dbl, P, P]
     lib.oracle_train_epoch_softmax.restype = ctypes.c_int
+    lib.oracle_grab_stale_mean.argtypes = [i64, i64, P, P, P, P, P, P, P, P, P, P]
+    lib.oracle_grab_stale_mean.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -200,3 +202,24 @@ def train_epoch_softmax(X: np.ndarray, y: np.ndarray, perm_in: np.ndarray | None
         raise ValueError("oracle_train_epoch_softmax failed")
     bal = server_epoch(rows, perm_in)
     return {"W": W, "v": v, "rows": rows, "loss": loss, "eps": bal["eps"], "perm": bal["perm"], "r": bal["r"]}
+
+
+def grab_stale_mean(g: np.ndarray, stale_mean: np.ndarray | None = None, perm_in: np.ndarray | None = None):
+    """Centralized GraB balancing of g[n][d] centred by stale_mean.  Returns dict with
+    s [n] int8, r [d], perm [n], mean [d], t, norm_r, norm_z [n]."""
+    g = _c(g, np.float32)
+    n, d = g.shape
+    if stale_mean is not None:
+        stale_mean = _c(stale_mean, np.float32)
+    if perm_in is not None:
+        perm_in = _c(perm_in, np.int32)
+    s = np.zeros(n, np.int8)
+    r = np.zeros(d)
+    perm = np.zeros(n, np.int32)
+    mean = np.zeros(d)
+    t, nr, nz = np.zeros(n), np.zeros(n), np.zeros(n)
+    rc = _load().oracle_grab_stale_mean(n, d, _p(g), _p(stale_mean), _p(perm_in), _p(s), _p(r), _p(perm),
+                                        _p(mean), _p(t), _p(nr), _p(nz))
+    if rc != 0:
+        raise ValueError("oracle_grab_stale_mean failed")
+    return {"s": s, "r": r, "perm": perm, "mean": mean, "t": t, "norm_r": nr, "norm_z": nz}

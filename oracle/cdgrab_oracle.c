@@ -32,6 +32,8 @@
  *                             linear model (the per-example gradient a worker
  *                             computes in "CD-GraB Workers", line 4).
  *   oracle_parallel_herding   the parallel herding objective (Sec. 3.2).
+ *   oracle_grab_stale_mean    centralized GraB balancing (Sec. 2.1): vectors centred
+ *                             by a stale mean, greedy sign per vector, reorder.
  *   oracle_train_epoch_softmax  "CD-GraB Workers" + "CD-GraB Parameter Server"
  *                             (Sec. 3.3) for the softmax-regression model: per
  *                             step, m per-example gradients at the current
@@ -379,4 +381,45 @@ int oracle_train_epoch_softmax(int64_t m, int64_t n, int64_t in_dim, int64_t cla
     }
     free(delta); free(gbar);
     return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Centralized GraB balancing of one worker's n vectors (Sec. 2.1): the herding
+ * framework is run on z_j = g_j - stale_mean (the stale mean is last epoch's average
+ * gradient), each z_j gets the sign of the greedy rule of App. B.2, and the next
+ * order is the reorder of Sec. 2.1 under those signs.
+ *   g [n][d] fp32 in visiting order, stale_mean [d] fp32 or NULL (zero)
+ *   perm_in [n] or NULL, s_out [n] signs, r_out [d] final running sum,
+ *   perm_out [n], mean_out [d] or NULL: mean of g (the next stale mean),
+ *   t_out, nr_out, nz_out [n] or NULL: <r,z_j>, ||r|| before, ||z_j||. */
+int oracle_grab_stale_mean(int64_t n, int64_t d, const float *g, const float *stale_mean,
+                           const int32_t *perm_in, int8_t *s_out, double *r_out,
+                           int32_t *perm_out, double *mean_out, double *t_out,
+                           double *nr_out, double *nz_out)
+{
+    if (n < 1 || d < 1) return -1;
+    double *r = (double *)calloc((size_t)d, sizeof(double));
+    double *z = (double *)malloc((size_t)d * sizeof(double));
+    if (!r || !z) { free(r); free(z); return -1; }
+    for (int64_t j = 0; j < n; ++j) {
+        for (int64_t e = 0; e < d; ++e)
+            z[e] = (double)g[j * d + e] - (stale_mean ? (double)stale_mean[e] : 0.0);
+        double t, nr, nz;
+        int s = oracle_greedy_balance(d, r, z, &t, &nr, &nz);
+        s_out[j] = (int8_t)s;
+        if (t_out) t_out[j] = t;
+        if (nr_out) nr_out[j] = nr;
+        if (nz_out) nz_out[j] = nz;
+    }
+    int rc = oracle_reorder(n, s_out, perm_in, perm_out);
+    if (mean_out) {
+        for (int64_t e = 0; e < d; ++e) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < n; ++j) acc += (double)g[j * d + e];
+            mean_out[e] = acc / (double)n;
+        }
+    }
+    memcpy(r_out, r, (size_t)d * sizeof(double));
+    free(r); free(z);
+    return rc;
 }

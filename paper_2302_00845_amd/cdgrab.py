@@ -86,6 +86,8 @@ def load_library():
     lib.cdgrab_balance_epoch.restype = ctypes.c_int
     lib.cdgrab_reorder.argtypes = [P, i64, i64, P, P, P]
     lib.cdgrab_reorder.restype = ctypes.c_int
+    lib.cdgrab_balance_epoch_stale_mean.argtypes = [P, i64, i64, P, P, P, P, P, P, P]
+    lib.cdgrab_balance_epoch_stale_mean.restype = ctypes.c_int
     lib.cdgrab_balance_epoch_independent.argtypes = [P, i64, i64, i64, P, P, P, P]
     lib.cdgrab_balance_epoch_independent.restype = ctypes.c_int
     lib.cdgrab_train_epoch_softmax.argtypes = [P, i64, i64, i64, i64, P, P, P, P, P, ctypes.c_float,
@@ -93,6 +95,8 @@ def load_library():
     lib.cdgrab_train_epoch_softmax.restype = ctypes.c_int
     lib.cdgrab_herding_bound.argtypes = [P, i64, i64, i64, P, P, P]
     lib.cdgrab_herding_bound.restype = ctypes.c_int
+    lib.cdgrab_measure_read_bandwidth.argtypes = [P, i64, ctypes.POINTER(ctypes.c_double)]
+    lib.cdgrab_measure_read_bandwidth.restype = ctypes.c_int
     lib.cdgrab_get_timing.argtypes = [P, ctypes.POINTER(Timing)]
     lib.cdgrab_get_timing.restype = ctypes.c_int
     _lib = lib
@@ -157,6 +161,12 @@ class Handle:
     def _check(self, rc: int):
         if rc != CDGRAB_OK:
             raise CdgrabError(rc, self._lib.cdgrab_last_error(self._h).decode())
+
+    def measure_read_bandwidth(self, nbytes: int = 2 << 30) -> float:
+        """GB/s of a plain streaming read over a scratch buffer (the practical ceiling)."""
+        out = ctypes.c_double()
+        self._check(self._lib.cdgrab_measure_read_bandwidth(self._h, nbytes, ctypes.byref(out)))
+        return out.value
 
     def timing(self) -> dict:
         t = Timing()
@@ -269,3 +279,21 @@ def cdgrab_balance_epoch_independent(h: Handle, grads: torch.Tensor,
         h._h, m, n, d, _ptr(grads, torch.float32, (m, n, d), "grads", h.device),
         _ptr(perm_in, torch.int32, (m, n), "perm_in", h.device), signs.data_ptr(), perm.data_ptr()))
     return {"signs": signs, "perm": perm}
+
+
+def cdgrab_balance_epoch_stale_mean(h: Handle, grads: torch.Tensor,
+                                    stale_mean: Optional[torch.Tensor] = None,
+                                    perm_in: Optional[torch.Tensor] = None) -> dict:
+    """Centralized GraB balancing of grads[n][d] centred by a stale mean."""
+    n, d = grads.shape
+    dev = h.device
+    signs = torch.empty((n,), dtype=torch.int8, device=dev)
+    perm = torch.empty((n,), dtype=torch.int32, device=dev)
+    mean = torch.empty((d,), dtype=torch.float32, device=dev)
+    r64 = torch.empty((d,), dtype=torch.float64, device=dev)
+    h._check(h._lib.cdgrab_balance_epoch_stale_mean(
+        h._h, n, d, _ptr(grads, torch.float32, (n, d), "grads", dev),
+        _ptr(stale_mean, torch.float32, (d,), "stale_mean", dev),
+        _ptr(perm_in, torch.int32, (n,), "perm_in", dev),
+        signs.data_ptr(), perm.data_ptr(), mean.data_ptr(), r64.data_ptr()))
+    return {"signs": signs, "perm": perm, "mean": mean, "r64": r64}

@@ -46,6 +46,7 @@ struct cdgrab_handle {
     double *reduced = nullptr;                            // kReduceSlices x PartLayout<64>::PART doubles
     int8_t *eps_blk = nullptr;                            // up to 64 signs of the current block
     int32_t *flag = nullptr;                              // reorder's bad-sign flag
+    float *zero_row = nullptr; int64_t zero_row_cap = 0;  // a zero vector standing in for a missing stale mean
     float *train_delta = nullptr; int64_t train_delta_cap = 0;  // [m][classes] softmax deltas of one step
     double *herd_ws = nullptr; int64_t herd_cap = 0;      // herding evaluator: segment sums, starts, mean
     float *staging = nullptr;  int64_t staging_cap = 0;   // floats
@@ -268,6 +269,7 @@ int cdgrab_destroy(cdgrab_handle *h) {
     if (h->flag) (void)hipFree(h->flag);
     if (h->herd_ws) (void)hipFree(h->herd_ws);
     if (h->train_delta) (void)hipFree(h->train_delta);
+    if (h->zero_row) (void)hipFree(h->zero_row);
     if (h->staging) (void)hipFree(h->staging);
     delete h;
     return CDGRAB_OK;
@@ -303,10 +305,14 @@ int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
 
 // One epoch.  With a generator, `chunk_pairs` flattened pairs are staged per callback
 // (0 = one block) and balanced block by block out of the staging buffer.
+// With `center_row` (dense input, m == 1) every row j is paired with that one row
+// instead of with its neighbour: "pair" j is (row j, center_row), n pairs in all, and
+// the permutation is left to the caller (perm_out may be null).
 static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *grads,
                               cdgrab_gen_fn gen, void *gen_ctx, int64_t chunk_pairs,
                               const int32_t *perm_in, int8_t *signs_out, int32_t *perm_out,
-                              float *r_out, double *r64_out, double *dots_out) {
+                              float *r_out, double *r64_out, double *dots_out,
+                              const float *center_row = nullptr) {
     if (!h) return CDGRAB_EINVAL;
     if (m < 1 || n < 2 || (n & 1) || d < 1)
         return fail(h, CDGRAB_EINVAL,
@@ -314,7 +320,7 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                     (long long)m, (long long)n, (long long)d);
     if ((grads == nullptr) == (gen == nullptr))
         return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: give exactly one of grads and gen");
-    if (!signs_out || !perm_out)
+    if (!signs_out || (!perm_out && !center_row))
         return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: signs_out and perm_out are required");
     if (n > INT32_MAX) return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: n exceeds int32 range");
     HIP_TRY(h, hipSetDevice(h->device));
@@ -324,6 +330,7 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     int64_t align = 16;
     if (!streamed) {
         uintptr_t a = reinterpret_cast<uintptr_t>(grads);
+        if (center_row) a |= reinterpret_cast<uintptr_t>(center_row);
         align = (a % 16 == 0) ? 16 : (a % 8 == 0) ? 8 : 4;
         if (a % 4) return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: grads is not 4-byte aligned");
     }
@@ -371,6 +378,11 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
             for (int j = 0; j < rm.nb; ++j) {
                 if (streamed) {
                     rm.off[2 * j] = (int64_t)(2 * j) * d;
+                } else if (center_row) {
+                    rm.off[2 * j] = (p0 + j) * d;
+                    rm.off[2 * j + 1] = (int64_t)((reinterpret_cast<intptr_t>(center_row) -
+                                                   reinterpret_cast<intptr_t>(grads)) / (intptr_t)sizeof(float));
+                    continue;
                 } else {
                     const int64_t p = p0 + j, k = p / m, i = p - k * m;
                     rm.off[2 * j] = (i * n + 2 * k) * d;
@@ -387,8 +399,9 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     MARK(h, 1, kFinish);
     {
         int64_t work = m * (n / 2);
-        hipLaunchKernelGGL(build_pair_permutations, dim3((unsigned)((work + 255) / 256)), dim3(256), 0,
-                           h->stream, signs_out, perm_in, perm_out, m, n);
+        if (!center_row)
+            hipLaunchKernelGGL(build_pair_permutations, dim3((unsigned)((work + 255) / 256)), dim3(256), 0,
+                               h->stream, signs_out, perm_in, perm_out, m, n);
         if (r_out || r64_out)
             hipLaunchKernelGGL(export_running_sum, dim3((unsigned)std::min<int64_t>(8192, (d + 255) / 256)),
                                dim3(256), 0, h->stream, h->r_sum, d, r_out, r64_out);
@@ -411,6 +424,40 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
                          double *dots_out) {
     return balance_epoch_impl(h, m, n, d, grads, gen, gen_ctx, 0, perm_in, signs_out, perm_out, r_out,
                               r64_out, dots_out);
+}
+
+int cdgrab_balance_epoch_stale_mean(cdgrab_handle *h, int64_t n, int64_t d, const float *grads,
+                                    const float *stale_mean, const int32_t *perm_in,
+                                    int8_t *signs_out, int32_t *perm_out, float *mean_out,
+                                    double *r64_out) {
+    if (!h) return CDGRAB_EINVAL;
+    if (n < 1 || d < 1 || n > INT32_MAX / 2)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_stale_mean: need n>=1, d>=1");
+    if (!grads || !signs_out || !perm_out)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_stale_mean: null pointer");
+    HIP_TRY(h, hipSetDevice(h->device));
+    int rc = CDGRAB_OK;
+    if (!stale_mean) {
+        rc = ensure(h, h->zero_row, h->zero_row_cap, d);
+        if (rc) return rc;
+        HIP_TRY(h, hipMemsetAsync(h->zero_row, 0, (size_t)d * sizeof(float), h->stream));
+        stale_mean = h->zero_row;
+    }
+    if (!h->flag) { int64_t cap = 0; rc = ensure(h, h->flag, cap, (int64_t)1); if (rc) return rc; }
+    // single vectors as pairs (g_j, stale mean): the pair walk then balances
+    // mean - g_j = -z_j and its exported sign is minus the sign of z_j, ties included
+    rc = balance_epoch_impl(h, 1, 2 * n, d, grads, nullptr, nullptr, 0, nullptr, signs_out, nullptr, nullptr,
+                            r64_out, nullptr, stale_mean);
+    if (rc) return rc;
+    hipLaunchKernelGGL(negate_signs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, h->stream, signs_out, n);
+    HIP_TRY(h, hipMemsetAsync(h->flag, 0, sizeof(int32_t), h->stream));
+    hipLaunchKernelGGL(reorder_from_signs, dim3(1), dim3(kScanThreads), 0, h->stream, signs_out, perm_in,
+                       perm_out, n, h->flag);
+    if (mean_out)
+        hipLaunchKernelGGL(column_mean, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, h->stream, grads, n, d,
+                           mean_out);
+    HIP_TRY(h, hipGetLastError());
+    return CDGRAB_OK;
 }
 
 int cdgrab_balance_epoch_independent(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
@@ -530,6 +577,39 @@ int cdgrab_herding_bound(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
                        segsum, sh, zbar, start);
     hipLaunchKernelGGL(herding_prefix_max, dim3(grid), dim3(256), 0, h->stream, z, perm, sh, zbar, start, bits);
     HIP_TRY(h, hipGetLastError());
+    return CDGRAB_OK;
+}
+
+int cdgrab_measure_read_bandwidth(cdgrab_handle *h, int64_t bytes, double *gb_per_s_out) {
+    if (!h || !gb_per_s_out) return CDGRAB_EINVAL;
+    if (bytes < (1 << 20) || bytes > ((int64_t)64 << 30))
+        return fail(h, CDGRAB_EINVAL, "cdgrab_measure_read_bandwidth: bytes must be between 1 MiB and 64 GiB");
+    HIP_TRY(h, hipSetDevice(h->device));
+    const int64_t count4 = bytes / 16;
+    float *buf = nullptr;
+    if (hipMalloc(reinterpret_cast<void **>(&buf), (size_t)count4 * 16 + 16) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(h, CDGRAB_ENOMEM, "cdgrab_measure_read_bandwidth: cannot allocate %lld bytes", (long long)bytes);
+    }
+    hipEvent_t e0, e1;
+    HIP_TRY(h, hipEventCreate(&e0));
+    HIP_TRY(h, hipEventCreate(&e1));
+    HIP_TRY(h, hipMemsetAsync(buf, 0, (size_t)count4 * 16 + 16, h->stream));
+    const int reps = 5;
+    const dim3 grid((unsigned)(h->num_cu * 8));
+    const float4_t *src = reinterpret_cast<const float4_t *>(buf);
+    hipLaunchKernelGGL(stream_read_probe, grid, dim3(kThreads), 0, h->stream, src, count4, buf + count4 * 4);
+    HIP_TRY(h, hipEventRecord(e0, h->stream));
+    for (int q = 0; q < reps; ++q)
+        hipLaunchKernelGGL(stream_read_probe, grid, dim3(kThreads), 0, h->stream, src, count4, buf + count4 * 4);
+    HIP_TRY(h, hipEventRecord(e1, h->stream));
+    HIP_TRY(h, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(h, hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    HIP_TRY(h, hipFree(buf));
+    *gb_per_s_out = (double)count4 * 16.0 * reps / ((double)ms * 1e-3) / 1e9;
     return CDGRAB_OK;
 }
 

@@ -80,6 +80,21 @@ __global__ __launch_bounds__(kScanThreads) void reorder_from_signs(const int8_t 
     }
 }
 
+// s <- -s for n signs (the pair walk exports the sign of a pair's second row).
+__global__ void negate_signs(int8_t *__restrict__ signs, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) signs[i] = (int8_t)(-signs[i]);
+}
+
+// mean_out[e] = (1/n) sum_j rows[j][e], accumulated in double, one thread per element.
+__global__ void column_mean(const float *__restrict__ rows, int64_t n, int64_t d, float *__restrict__ mean_out) {
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= d) return;
+    double acc = 0.0;
+    for (int64_t j = 0; j < n; ++j) acc += (double)rows[j * d + e];
+    mean_out[e] = (float)(acc / (double)n);
+}
+
 // ---------------------------------------------------------------------------
 // Per-example gradient of softmax cross-entropy for a linear model ("CD-GraB
 // Workers", line 4).  One wavefront per example: the example's features are

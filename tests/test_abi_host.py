@@ -32,7 +32,8 @@ def test_header_declares_the_expected_calls():
     for required in ("cdgrab_pergrad", "cdgrab_balance_epoch", "cdgrab_reorder", "cdgrab_create",
                      "cdgrab_destroy", "cdgrab_last_error", "cdgrab_plan_epoch", "cdgrab_get_timing",
                      "cdgrab_herding_bound", "cdgrab_train_epoch_softmax",
-                     "cdgrab_balance_epoch_independent"):
+                     "cdgrab_balance_epoch_independent", "cdgrab_measure_read_bandwidth",
+                     "cdgrab_balance_epoch_stale_mean"):
         assert required in names
 
 

@@ -113,3 +113,37 @@ def test_synthetic_herding_study_reduced(lib):
         print("m=%d random %.2f  epochs %s" % (m, np.mean(rand), ["%.2f" % b for b in bounds]))
         assert bounds[-1] < 0.25 * min(rand)
         assert min(bounds[1:]) < bounds[0]
+
+
+@pytest.mark.parametrize("n,d,exact", [(1, 1, True), (7, 3, True), (33, 100, True), (100, 1000, True),
+                                       (64, 5000, False), (257, 300, False)])
+def test_stale_mean_balance_matches_oracle(lib, n, d, exact):
+    """Centralized GraB balancing (single vectors centred by a stale mean)."""
+    h = lib.Handle()
+    rng = np.random.default_rng(n + d)
+    if exact:
+        g = rng.integers(-6, 7, size=(n, d)).astype(np.float32)
+        mu = rng.integers(-2, 3, size=d).astype(np.float32)
+    else:
+        g = workloads.heavy_rows(n, 1, n, d)[0]
+        mu = g.mean(0).astype(np.float32) + 0.01 * rng.standard_normal(d).astype(np.float32)
+    perm_in = rng.permutation(n).astype(np.int32)
+    out = lib.cdgrab_balance_epoch_stale_mean(h, torch.from_numpy(g).cuda(), torch.from_numpy(mu).cuda(),
+                                              torch.from_numpy(perm_in).cuda())
+    ref = oracle.grab_stale_mean(g, mu, perm_in)
+    s = out["signs"].cpu().numpy()
+    if not np.array_equal(s, ref["s"]):
+        assert not exact
+        first = int(np.nonzero(s != ref["s"])[0][0])          # only a near-tie may differ first
+        assert abs(ref["t"][first]) <= 1e-9 * ref["norm_r"][first] * ref["norm_z"][first]
+    else:
+        np.testing.assert_allclose(out["r64"].cpu().numpy(), ref["r"], rtol=0,
+                                   atol=1e-12 * max(1.0, np.abs(ref["r"]).max()))
+        assert np.array_equal(out["perm"].cpu().numpy(), ref["perm"])
+    assert np.array_equal(out["perm"].cpu().numpy(), oracle.reorder(s, perm_in))
+    np.testing.assert_allclose(out["mean"].cpu().numpy(), ref["mean"], rtol=1e-6, atol=1e-7)
+    # no stale mean given = zero mean
+    out0 = lib.cdgrab_balance_epoch_stale_mean(h, torch.from_numpy(g).cuda())
+    ref0 = oracle.grab_stale_mean(g)
+    if exact:
+        assert np.array_equal(out0["signs"].cpu().numpy(), ref0["s"])

@@ -414,3 +414,41 @@ def test_train_epoch_against_autograd_sgd():
     # the balancing attached to the epoch is the plain server walk on those rows
     ref = oracle.server_epoch(out["rows"], perm)
     assert np.array_equal(ref["eps"], out["eps"]) and np.array_equal(ref["perm"], out["perm"])
+
+
+# --------------------------------------------------------------------------- GraB with a stale mean
+def test_grab_stale_mean_hand_case_and_brute_force():
+    """Hand case (d=1, mean 2): vectors 5,1,2,4 -> z = 3,-1,0,2.
+    z=3: r=0 tie -> s=-1, r=-3.  z=-1: |-4|=4 vs |-2|=2, not "<" -> s=-1, r=-2.
+    z=0: tie -> s=-1, r=-2.  z=2: |0| < |-4| -> s=+1, r=0.
+    L_pos=[3], L_neg=[0,1,2] -> order [3,2,1,0]."""
+    g = np.array([[5.0], [1.0], [2.0], [4.0]], np.float32)
+    out = oracle.grab_stale_mean(g, np.array([2.0], np.float32))
+    assert out["s"].tolist() == [-1, -1, -1, 1]
+    assert out["r"].tolist() == [0.0] and out["perm"].tolist() == [3, 2, 1, 0]
+    assert out["mean"].tolist() == [3.0]
+    # exact-integer brute force: literal norm comparison, list reorder
+    rng = np.random.default_rng(3)
+    for n, d in [(1, 1), (7, 3), (20, 9)]:
+        g = rng.integers(-6, 7, size=(n, d)).astype(np.float32)
+        mu = rng.integers(-2, 3, size=d).astype(np.float32)
+        perm_in = rng.permutation(n).astype(np.int32)
+        r = [0] * d
+        signs = []
+        for j in range(n):
+            z = [int(a) - int(b) for a, b in zip(g[j], mu)]
+            plus = sum((x + y) ** 2 for x, y in zip(r, z))
+            minus = sum((x - y) ** 2 for x, y in zip(r, z))
+            s = 1 if plus < minus else -1
+            r = [x + s * y for x, y in zip(r, z)]
+            signs.append(s)
+        pos = [int(perm_in[j]) for j in range(n) if signs[j] == 1]
+        neg = [int(perm_in[j]) for j in range(n) if signs[j] == -1]
+        out = oracle.grab_stale_mean(g, mu, perm_in)
+        assert out["s"].tolist() == signs and out["r"].tolist() == [float(v) for v in r]
+        assert out["perm"].tolist() == pos + neg[::-1]
+        np.testing.assert_allclose(out["mean"], g.astype(np.float64).mean(0), rtol=1e-15)
+    # no stale mean = zero mean
+    a = oracle.grab_stale_mean(g)
+    b = oracle.grab_stale_mean(g, np.zeros(g.shape[1], np.float32))
+    assert a["s"].tolist() == b["s"].tolist() and a["perm"].tolist() == b["perm"].tolist()
