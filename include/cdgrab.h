@@ -149,6 +149,20 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                          int32_t *perm_out, float *r_out, double *r64_out,
                          double *dots_out);
 
+/* The epoch of cdgrab_balance_epoch with the randomized sign rule of the analysis
+ * (PairBalance with its RandomizedBalance subroutine, Sec. 3.2; the paper's
+ * experiments use the greedy rule instead): for c = z1 - z2 the first row gets +1
+ * with probability p = (1 - <r,c>)/2, so the exported sign is
+ *     eps = -1 if u < (1 + t)/2 else +1,     t = <r, z2 - z1>,
+ * with u the caller's draw for that pair (a p outside [0,1] decides by itself; the
+ * rule is meant for vectors of norm <= 1).  Dense input only.
+ *   uniforms [m][n/2] fp32 dev, each in [0,1); other arguments as cdgrab_balance_epoch.
+ * Errors: as cdgrab_balance_epoch, EINVAL for a null uniforms. */
+int cdgrab_balance_epoch_randomized(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
+                                    const float *grads, const float *uniforms,
+                                    const int32_t *perm_in, int8_t *signs_out, int32_t *perm_out,
+                                    double *r64_out, double *dots_out);
+
 /* Centralized GraB balancing with a stale mean (Sec. 2.1: the prior method this
  * paper builds on; run per worker it is the ablation's "ID-GraB (Bal)" with the
  * deterministic rule).  One worker, n vectors (n may be odd):

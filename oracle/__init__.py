@@ -58,6 +58,8 @@ def _load():
     lib.oracle_parallel_herding.restype = dbl
     lib.oracle_train_epoch_softmax.argtypes = [i64, i64, i64, i64, P, P, P, P, P, dbl, dbl, P, P]
     lib.oracle_train_epoch_softmax.restype = ctypes.c_int
+    lib.oracle_randomized_epoch.argtypes = [i64, i64, i64, P, P, P, P, P, P, P]
+    lib.oracle_randomized_epoch.restype = ctypes.c_int
     lib.oracle_grab_stale_mean.argtypes = [i64, i64, P, P, P, P, P, P, P, P, P, P]
     lib.oracle_grab_stale_mean.restype = ctypes.c_int
     _lib = lib
@@ -223,3 +225,22 @@ def grab_stale_mean(g: np.ndarray, stale_mean: np.ndarray | None = None, perm_in
     if rc != 0:
         raise ValueError("oracle_grab_stale_mean failed")
     return {"s": s, "r": r, "perm": perm, "mean": mean, "t": t, "norm_r": nr, "norm_z": nz}
+
+
+def randomized_epoch(z: np.ndarray, u: np.ndarray, perm_in: np.ndarray | None = None):
+    """Server walk with the RandomizedBalance subroutine and the given uniform draws
+    u[m][n/2].  Returns dict eps, r, perm, t (t = <r, z2 - z1> at decision time)."""
+    z = _c(z, np.float32)
+    u = _c(u, np.float32)
+    m, n, d = z.shape
+    assert u.shape == (m, n // 2)
+    if perm_in is not None:
+        perm_in = _c(perm_in, np.int32)
+    eps = np.zeros((m, n // 2), np.int8)
+    r = np.zeros(d)
+    perm = np.zeros((m, n), np.int32)
+    t = np.zeros((m, n // 2))
+    rc = _load().oracle_randomized_epoch(m, n, d, _p(z), _p(u), _p(perm_in), _p(eps), _p(r), _p(perm), _p(t))
+    if rc != 0:
+        raise ValueError("oracle_randomized_epoch failed")
+    return {"eps": eps, "r": r, "perm": perm, "t": t}

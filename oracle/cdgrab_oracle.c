@@ -32,6 +32,8 @@
  *                             linear model (the per-example gradient a worker
  *                             computes in "CD-GraB Workers", line 4).
  *   oracle_parallel_herding   the parallel herding objective (Sec. 3.2).
+ *   oracle_randomized_epoch   the server walk with PairBalance's RandomizedBalance
+ *                             subroutine (Sec. 3.2) and caller-supplied uniform draws.
  *   oracle_grab_stale_mean    centralized GraB balancing (Sec. 2.1): vectors centred
  *                             by a stale mean, greedy sign per vector, reorder.
  *   oracle_train_epoch_softmax  "CD-GraB Workers" + "CD-GraB Parameter Server"
@@ -421,5 +423,56 @@ int oracle_grab_stale_mean(int64_t n, int64_t d, const float *g, const float *st
     }
     memcpy(r_out, r, (size_t)d * sizeof(double));
     free(r); free(z);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------- */
+/* RandomizedBalance (subroutine of PairBalance, Sec. 3.2): p = (1 - <r,c>)/2;
+ * s = +1 with probability p, else -1; r <- r + s c.  The draw is the caller's
+ * uniform u in [0,1): s = +1 iff u < p. */
+int oracle_randomized_balance(int64_t d, double *r, const double *c, double u, double *t_out)
+{
+    double t = 0.0;
+    for (int64_t e = 0; e < d; ++e) t += r[e] * c[e];
+    double p = (1.0 - t) / 2.0;
+    int s = (u < p) ? +1 : -1;
+    for (int64_t e = 0; e < d; ++e) r[e] += (double)s * c[e];
+    if (t_out) *t_out = t;
+    return s;
+}
+
+/* The one-step server walk (App. C.1 loop nest) with that subroutine.
+ *   z [m][n][d], u [m][n/2] draws, perm_in [m][n] or NULL
+ *   eps_out [m][n/2]: exported sign (of the second row) = -s, r_out [d], perm_out [m][n],
+ *   t_out [m][n/2] or NULL: <r, z2 - z1> seen at decision time. */
+int oracle_randomized_epoch(int64_t m, int64_t n, int64_t d, const float *z, const float *u,
+                            const int32_t *perm_in, int8_t *eps_out, double *r_out,
+                            int32_t *perm_out, double *t_out)
+{
+    if (m < 1 || n < 2 || (n & 1) || d < 1) return -1;
+    double *h = (double *)calloc((size_t)d, sizeof(double));
+    double *c = (double *)malloc((size_t)d * sizeof(double));
+    int8_t *per_example = (int8_t *)malloc((size_t)n);
+    if (!h || !c || !per_example) { free(h); free(c); free(per_example); return -1; }
+    for (int64_t j = 2; j <= n; j += 2)
+        for (int64_t i = 0; i < m; ++i) {
+            const float *z1 = z + (i * n + (j - 2)) * d, *z2 = z + (i * n + (j - 1)) * d;
+            for (int64_t e = 0; e < d; ++e) c[e] = (double)z1[e] - (double)z2[e];
+            int64_t o = i * (n / 2) + (j / 2 - 1);
+            double t;
+            int s = oracle_randomized_balance(d, h, c, (double)u[o], &t);
+            eps_out[o] = (int8_t)(-s);
+            if (t_out) t_out[o] = -t;
+        }
+    int rc = 0;
+    for (int64_t i = 0; i < m && rc == 0; ++i) {
+        for (int64_t k = 0; k < n / 2; ++k) {         /* first row gets s = -eps, second -s = eps */
+            per_example[2 * k] = (int8_t)(-eps_out[i * (n / 2) + k]);
+            per_example[2 * k + 1] = eps_out[i * (n / 2) + k];
+        }
+        rc = oracle_reorder(n, per_example, perm_in ? perm_in + i * n : NULL, perm_out + i * n);
+    }
+    memcpy(r_out, h, (size_t)d * sizeof(double));
+    free(h); free(c); free(per_example);
     return rc;
 }

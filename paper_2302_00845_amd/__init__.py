@@ -9,6 +9,7 @@ from .cdgrab import (  # noqa: F401
     Handle,
     cdgrab_balance_epoch,
     cdgrab_balance_epoch_independent,
+    cdgrab_balance_epoch_randomized,
     cdgrab_balance_epoch_stale_mean,
     cdgrab_herding_bound,
     cdgrab_pergrad,

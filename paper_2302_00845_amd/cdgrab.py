@@ -86,6 +86,8 @@ def load_library():
     lib.cdgrab_balance_epoch.restype = ctypes.c_int
     lib.cdgrab_reorder.argtypes = [P, i64, i64, P, P, P]
     lib.cdgrab_reorder.restype = ctypes.c_int
+    lib.cdgrab_balance_epoch_randomized.argtypes = [P, i64, i64, i64, P, P, P, P, P, P, P]
+    lib.cdgrab_balance_epoch_randomized.restype = ctypes.c_int
     lib.cdgrab_balance_epoch_stale_mean.argtypes = [P, i64, i64, P, P, P, P, P, P, P]
     lib.cdgrab_balance_epoch_stale_mean.restype = ctypes.c_int
     lib.cdgrab_balance_epoch_independent.argtypes = [P, i64, i64, i64, P, P, P, P]
@@ -297,3 +299,20 @@ def cdgrab_balance_epoch_stale_mean(h: Handle, grads: torch.Tensor,
         _ptr(perm_in, torch.int32, (n,), "perm_in", dev),
         signs.data_ptr(), perm.data_ptr(), mean.data_ptr(), r64.data_ptr()))
     return {"signs": signs, "perm": perm, "mean": mean, "r64": r64}
+
+
+def cdgrab_balance_epoch_randomized(h: Handle, grads: torch.Tensor, uniforms: torch.Tensor,
+                                    perm_in: Optional[torch.Tensor] = None) -> dict:
+    """cdgrab_balance_epoch with the randomized sign rule; uniforms[m][n/2] in [0,1)."""
+    m, n, d = grads.shape
+    dev = h.device
+    signs = torch.empty((m, n // 2), dtype=torch.int8, device=dev)
+    perm = torch.empty((m, n), dtype=torch.int32, device=dev)
+    r64 = torch.empty((d,), dtype=torch.float64, device=dev)
+    dots = torch.empty((m, n // 2), dtype=torch.float64, device=dev)
+    h._check(h._lib.cdgrab_balance_epoch_randomized(
+        h._h, m, n, d, _ptr(grads, torch.float32, (m, n, d), "grads", dev),
+        _ptr(uniforms, torch.float32, (m, n // 2), "uniforms", dev),
+        _ptr(perm_in, torch.int32, (m, n), "perm_in", dev),
+        signs.data_ptr(), perm.data_ptr(), r64.data_ptr(), dots.data_ptr()))
+    return {"signs": signs, "perm": perm, "r64": r64, "dots": dots}

@@ -281,13 +281,15 @@ __global__ __launch_bounds__(kThreads) void reduce_partials(const double *__rest
 // Sequential sign resolution.  All 256 threads finish the reduction and unpack
 // the Gram tiles into LDS; then one wavefront walks the block: lane k carries
 // t_k = <r, d_k> + sum_{j<k, decided} eps_j G[j][k]; step j broadcasts t_j,
-// fixes eps_j = +1 if t_j <= 0 else -1 and updates the later lanes.
+// fixes eps_j = +1 if t_j <= 0 else -1 (or, given uniform draws, the randomized
+// rule) and updates the later lanes.
 template <int BB>
 __global__ __launch_bounds__(kThreads) void resolve_signs(const double *__restrict__ sliced, int nb,
                                                           int64_t k0, int32_t i0, int32_t m, int64_t half_n,
                                                           int8_t *__restrict__ eps_blk,
                                                           int8_t *__restrict__ signs_out,
-                                                          double *__restrict__ dots_out)
+                                                          double *__restrict__ dots_out,
+                                                          const float *__restrict__ uniforms)
 {
     using L = PartLayout<BB>;
     __shared__ double G[BB][BB + 1];
@@ -317,24 +319,36 @@ __global__ __launch_bounds__(kThreads) void resolve_signs(const double *__restri
     double t = (lane < nb) ? P[lane] : 0.0;
     double my_t = 0.0;
     int my_eps = 0;
+    // flattened pair of this lane -> (worker, pair) slot of the [m][n/2] arrays
+    int64_t slot = 0;
+    if (lane < nb) {
+        uint32_t q = (uint32_t)(i0 + lane);
+        uint32_t dk = q / (uint32_t)m;
+        slot = (int64_t)(q - dk * (uint32_t)m) * half_n + (k0 + dk);
+    }
+    // randomized rule (PairBalance's RandomizedBalance subroutine, Sec. 3.2): with
+    // c = z1 - z2 = -d, the first row gets +1 with probability p = (1 - <r,c>)/2 =
+    // (1 + t)/2, so the exported sign (of the second row) is -1 when u < p.
+    const float my_u = (uniforms && lane < nb) ? uniforms[slot] : 0.f;
 #pragma unroll
     for (int j = 0; j < BB; ++j) {
         if (j < nb) {  // uniform
             const int lo = __builtin_amdgcn_readlane(__double2loint(t), j);
             const int hi = __builtin_amdgcn_readlane(__double2hiint(t), j);
             const double tj = __hiloint2double(hi, lo);
-            const int eps = (tj <= 0.0) ? 1 : -1;
+            int eps = (tj <= 0.0) ? 1 : -1;
+            if (uniforms) {
+                const float uj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_u), j));
+                eps = ((double)uj < 0.5 * (1.0 + tj)) ? -1 : 1;
+            }
             if (lane == j) { my_t = tj; my_eps = eps; }
             if (lane > j) t += (double)eps * col[j];
         }
     }
     if (lane < nb) {
-        uint32_t q = (uint32_t)(i0 + lane);
-        uint32_t dk = q / (uint32_t)m;
-        int64_t i = q - dk * (uint32_t)m, k = k0 + dk;
         eps_blk[lane] = (int8_t)my_eps;
-        signs_out[i * half_n + k] = (int8_t)my_eps;
-        if (dots_out) dots_out[i * half_n + k] = my_t;
+        signs_out[slot] = (int8_t)my_eps;
+        if (dots_out) dots_out[slot] = my_t;
     }
 }
 

@@ -46,6 +46,7 @@ struct cdgrab_handle {
     double *reduced = nullptr;                            // kReduceSlices x PartLayout<64>::PART doubles
     int8_t *eps_blk = nullptr;                            // up to 64 signs of the current block
     int32_t *flag = nullptr;                              // reorder's bad-sign flag
+    const float *uniforms = nullptr;                      // caller's draws while a randomized epoch runs
     float *zero_row = nullptr; int64_t zero_row_cap = 0;  // a zero vector standing in for a missing stale mean
     float *train_delta = nullptr; int64_t train_delta_cap = 0;  // [m][classes] softmax deltas of one step
     double *herd_ws = nullptr; int64_t herd_cap = 0;      // herding evaluator: segment sums, starts, mean
@@ -195,7 +196,7 @@ void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
 template <int BB>
 void launch_resolve(cdgrab_handle *h, const RowMap &rm, int8_t *signs_out, double *dots_out) {
     hipLaunchKernelGGL((resolve_signs<BB>), dim3(1), dim3(kThreads), 0, h->stream, h->reduced, rm.nb,
-                       rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out);
+                       rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out, h->uniforms);
 }
 
 template <int BB>
@@ -424,6 +425,19 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
                          double *dots_out) {
     return balance_epoch_impl(h, m, n, d, grads, gen, gen_ctx, 0, perm_in, signs_out, perm_out, r_out,
                               r64_out, dots_out);
+}
+
+int cdgrab_balance_epoch_randomized(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
+                                    const float *grads, const float *uniforms, const int32_t *perm_in,
+                                    int8_t *signs_out, int32_t *perm_out, double *r64_out,
+                                    double *dots_out) {
+    if (!h) return CDGRAB_EINVAL;
+    if (!uniforms) return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_randomized: uniforms is NULL");
+    h->uniforms = uniforms;
+    int rc = balance_epoch_impl(h, m, n, d, grads, nullptr, nullptr, 0, perm_in, signs_out, perm_out, nullptr,
+                                r64_out, dots_out);
+    h->uniforms = nullptr;
+    return rc;
 }
 
 int cdgrab_balance_epoch_stale_mean(cdgrab_handle *h, int64_t n, int64_t d, const float *grads,

@@ -125,3 +125,35 @@ def test_argument_errors(lib):
         lib.cdgrab_balance_epoch(h, 2, 4, 4)                      # neither grads nor generator
     with pytest.raises(lib.CdgrabError):
         lib.Handle(block_pairs=24)
+
+
+@pytest.mark.parametrize("m,n,d,bb", [(1, 4, 1, 0), (4, 40, 300, 16), (3, 70, 5000, 32), (16, 20, 130, 64)])
+def test_randomized_rule_matches_oracle(lib, m, n, d, bb):
+    """RandomizedBalance with caller-supplied draws against the oracle fed the same draws."""
+    import oracle
+    from parity import expected_perm_from_signs
+    rng = np.random.default_rng(m * n + d)
+    v = rng.standard_normal((m, n, d))
+    z = (v / (2 * np.linalg.norm(v, axis=2, keepdims=True))).astype(np.float32)
+    u = rng.random((m, n // 2)).astype(np.float32)
+    perm_in = workloads.random_perms(1, m, n)
+    h = lib.Handle(block_pairs=bb)
+    out = lib.cdgrab_balance_epoch_randomized(h, torch.from_numpy(z).cuda(), torch.from_numpy(u).cuda(),
+                                              torch.from_numpy(perm_in).cuda())
+    ref = oracle.randomized_epoch(z, u, perm_in)
+    eps = out["signs"].cpu().numpy()
+    if not np.array_equal(eps, ref["eps"]):
+        # only a draw within rounding of its threshold may decide differently first
+        flat_ref, flat_gpu = ref["eps"].T.reshape(-1), eps.T.reshape(-1)
+        first = int(np.nonzero(flat_ref != flat_gpu)[0][0])
+        t = ref["t"].T.reshape(-1)[first]
+        assert abs(float(u.T.reshape(-1)[first]) - 0.5 * (1 + t)) < 1e-9
+    else:
+        np.testing.assert_allclose(out["r64"].cpu().numpy(), ref["r"], atol=1e-12)
+        np.testing.assert_allclose(out["dots"].cpu().numpy(), ref["t"], atol=1e-12)
+        assert np.array_equal(out["perm"].cpu().numpy(), ref["perm"])
+    assert np.array_equal(out["perm"].cpu().numpy(), expected_perm_from_signs(eps, perm_in))
+    # the greedy entry point is unaffected by an earlier randomized call on the same handle
+    g = lib.cdgrab_balance_epoch(h, m, n, d, grads=torch.from_numpy(z).cuda(), want_r64=True, want_dots=True)
+    got = {k: (val.cpu().numpy() if val is not None else None) for k, val in g.items()}
+    check_epoch(z, got)

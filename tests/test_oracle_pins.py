@@ -452,3 +452,54 @@ def test_grab_stale_mean_hand_case_and_brute_force():
     a = oracle.grab_stale_mean(g)
     b = oracle.grab_stale_mean(g, np.zeros(g.shape[1], np.float32))
     assert a["s"].tolist() == b["s"].tolist() and a["perm"].tolist() == b["perm"].tolist()
+
+
+# --------------------------------------------------------------------------- randomized balancing
+def test_randomized_epoch_hand_case_and_probability():
+    """RandomizedBalance (Sec. 3.2): p = (1 - <r,c>)/2, s = +1 iff u < p.
+    Hand case, d=1, rows 0.5,0 | 0.25,0.75 with draws 0.3, 0.7:
+      pair 1: c=0.5, r=0 -> p=0.5, 0.3<0.5 -> s=+1, r=0.5 (first row to the front)
+      pair 2: c=-0.5, <r,c>=-0.25 -> p=0.625, 0.7 is not < p -> s=-1, r=1.0 (second row to the front)
+      order: front [0,3], back [1,2] reversed -> [0,3,2,1]; exported eps = -s = (-1,+1)."""
+    z = np.array([[[0.5], [0.0], [0.25], [0.75]]], np.float32)
+    out = oracle.randomized_epoch(z, np.array([[0.3, 0.7]], np.float32))
+    assert out["eps"].tolist() == [[-1, 1]] and out["r"].tolist() == [1.0]
+    assert out["perm"].tolist() == [[0, 3, 2, 1]]
+    # the other draws flip both decisions
+    out = oracle.randomized_epoch(z, np.array([[0.6, 0.1]], np.float32))
+    assert out["eps"].tolist() == [[1, -1]]          # s=-1 then (r=-0.5, c=-0.5: p=0.375) s=+1
+    # frequency of s=+1 at a fixed state: r=(0.8,0), c=(0.5,0.3): <r,c>=0.4 -> p=0.3
+    rng = np.random.default_rng(0)
+    # one-pair epochs cannot carry r; emulate with two pairs: pair 1 forces r, pair 2 is the trial
+    hits, trials = 0, 4000
+    for u2 in rng.random(trials).astype(np.float32):
+        zz = np.array([[[0.8, 0.0], [0.0, 0.0], [0.5, 0.3], [0.0, 0.0]]], np.float32)
+        o = oracle.randomized_epoch(zz, np.array([[0.0, u2]], np.float32))   # u=0 < p=0.5 -> s=+1, r=(0.8,0)
+        hits += int(o["eps"][0, 1] == -1)                                     # eps=-1 <=> s=+1
+    assert abs(hits / trials - 0.3) < 0.03
+
+
+def test_randomized_epoch_respects_the_balance_bound():
+    """Theorem 1 (as restated from Dwivedi & Mackey): for ||c|| <= 1 the signed prefix
+    sums stay below sqrt(2 log(4d/delta) log(4N/delta)) in the max norm w.p. 1-delta."""
+    rng = np.random.default_rng(1)
+    n, d = 2000, 16
+    v = rng.standard_normal((1, n, d))
+    v /= 2 * np.linalg.norm(v, axis=2, keepdims=True)          # ||z|| = 1/2, so ||z1 - z2|| <= 1
+    z = v.astype(np.float32)
+    u = rng.random((1, n // 2)).astype(np.float32)
+    out = oracle.randomized_epoch(z, u)
+    diffs = (z[0, 0::2].astype(np.float64) - z[0, 1::2].astype(np.float64))     # c = z1 - z2
+    s = -out["eps"][0].astype(np.float64)
+    prefix = np.cumsum(s[:, None] * diffs, axis=0)
+    np.testing.assert_allclose(prefix[-1], out["r"], atol=1e-12)
+    bound = np.sqrt(2 * np.log(4 * d / 0.01) * np.log(4 * (n // 2) / 0.01))
+    assert np.abs(prefix).max() < bound
+    # the walk is self-balancing: far below an unbalanced random-sign walk (~sqrt(N/d))
+    assert np.abs(prefix).max() < 3.0
+    # with the threshold w = 1 of the main text |<r,c>| does leave [-1, 1] now and then (the
+    # "Fail" branch of the appendix's version); p is then outside [0,1] and the draw cannot
+    # change the sign, which is the correcting one: s = -1 for <r,c> > 1, +1 for <r,c> < -1
+    t_c = -out["t"][0]                                          # <r, c>
+    forced = np.abs(t_c) > 1.0
+    assert np.all(s[forced] == -np.sign(t_c[forced]))
