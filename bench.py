@@ -40,6 +40,8 @@ def parse_args():
     ap.add_argument("--workload", default="c4_resnet18")
     ap.add_argument("--block-pairs", type=int, default=0)
     ap.add_argument("--pass1-groups", type=int, default=0)
+    ap.add_argument("--separate-passes", action="store_true",
+                    help="separate dot/Gram and apply launches per block instead of the fused launch")
     ap.add_argument("--n", type=int, default=0, help="override rows per worker (shorter epoch)")
     ap.add_argument("--seed", type=int, default=2302)
     ap.add_argument("--cpu-sample-pairs", type=int, default=-1,
@@ -170,7 +172,8 @@ def main():
     perm_in = torch.from_numpy(workloads.random_perms(args.seed, m, n)).to(dev)
     gen_fn = gen_ctx = grads = rows_src = None
     pergrad_ms = None
-    h = pkg.Handle(device=0, block_pairs=args.block_pairs, timing=1, pass1_groups=args.pass1_groups)
+    h = pkg.Handle(device=0, block_pairs=args.block_pairs, timing=1, pass1_groups=args.pass1_groups,
+                   separate_passes=args.separate_passes)
     if w.kind == "stream":
         rows_src = synth.from_workload(w, args.seed, n=n)
         gen_fn, gen_ctx = rows_src.device_callback(str(dev))
@@ -227,25 +230,33 @@ def main():
     roofline = None
     kernels = {}
     if not args.no_profile_step:
-        hp = pkg.Handle(device=0, block_pairs=args.block_pairs, timing=2, pass1_groups=args.pass1_groups)
+        hp = pkg.Handle(device=0, block_pairs=args.block_pairs, timing=2, pass1_groups=args.pass1_groups,
+                        separate_passes=args.separate_passes)
         if w.kind == "softmax":
             pkg.cdgrab_pergrad(hp, Xd, yd, Wd, G)
         pkg.cdgrab_balance_epoch(hp, m, n, d, grads=grads, gen=gen_fn, gen_ctx=gen_ctx, perm_in=perm_in)
         tp = hp.timing()
         pairs = N // 2
-        # algorithmic bytes per launch: both rows of every pair in the block (fp32)
-        # plus the double running sum (read in pass 1; read and written in pass 2)
         avg_pairs = pairs / blocks
-        bytes_p1 = 8.0 * avg_pairs * d + 8.0 * d
-        bytes_p2 = 8.0 * avg_pairs * d + 16.0 * d
-        for name, ms, nbytes in (("pass1_dots_gram", tp["pass1_ms"], bytes_p1),
-                                 ("pass2_apply", tp["pass2_ms"], bytes_p2)):
+        if args.separate_passes:
+            # algorithmic bytes per launch: both rows of every pair in the block (fp32) plus the
+            # double running sum (read in pass 1; read and written in pass 2)
+            per_kernel = (("pass1_dots_gram", tp["pass1_ms"], 8.0 * avg_pairs * d + 8.0 * d),
+                          ("pass2_apply", tp["pass2_ms"], 8.0 * avg_pairs * d + 16.0 * d))
+        else:
+            # fused launch: the rows of the previous block (apply) and of this block (dots + Gram),
+            # the running sum read once and written once.  The epoch's first launch has nothing to
+            # apply and its last block is applied by one stand-alone launch: together one more
+            # fused launch's worth of bytes, so all streaming time is divided by the block count.
+            per_kernel = (("pass1_dots_gram+apply", tp["pass1_ms"] + tp["pass2_ms"],
+                           16.0 * avg_pairs * d + 16.0 * d),)
+        for name, ms, nbytes in per_kernel:
             avg_ms = ms / blocks
             kernels[name] = {"avg_launch_ms": avg_ms, "algorithmic_bytes_per_launch": nbytes,
                              "achieved_GBs": nbytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else None}
         kernels["reduce_partials"] = {"avg_launch_ms": tp["reduce_ms"] / blocks}
         kernels["resolve_signs"] = {"avg_launch_ms": tp["resolve_ms"] / blocks}
-        dom = max(("pass1_dots_gram", "pass2_apply"), key=lambda k: kernels[k]["avg_launch_ms"])
+        dom = max((k[0] for k in per_kernel), key=lambda k: kernels[k]["avg_launch_ms"])
         traffic = read_traffic(args.workload)
         roofline = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["achieved_GBs"],
                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -259,8 +270,9 @@ def main():
     if roofline is not None:
         roofline["plain_read_GBs"] = read_ceiling
         roofline["frac_of_plain_read"] = roofline["achieved"] / read_ceiling
-    # whole balancer against the roofline: 8d + 12 d / Bb bytes per example
-    bytes_per_example = 8.0 * d + 12.0 * d / bb
+    # whole balancer against the roofline: 8d + 12 d / Bb bytes per example with separate passes
+    # (running sum read twice, written once per block), 8d + 8 d / Bb with the fused launch
+    bytes_per_example = 8.0 * d + (12.0 if args.separate_passes else 8.0) * d / bb
     balancer_gbs = bytes_per_example * N / (path_ms * 1e-3) / 1e9
 
     # the same epoch without the generator's cache drain (its write-back then lands in pass 1)
@@ -333,6 +345,7 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": args.workload, "m": m, "n": n, "d": d, "examples": N,
                    "block_pairs": bb, "blocks": blocks, "input": w.kind,
+                   "fused_apply": not args.separate_passes,
                    "input_drain": bool(w.kind == "stream" and not args.no_input_drain),
                    "rows_dtype": "f32", "parallelism": "1 GPU, m workers as a batch axis"},
         "generator_ms_per_step": gen_ms, "wall_ms_per_step": wall_ms,

@@ -42,6 +42,10 @@ typedef struct cdgrab_options {
     int32_t timing;      /* 0 off; 1 record events around generator / balancer work;
                             2 additionally around every balancer kernel               */
     int32_t pass1_groups; /* workgroups of the dot/Gram pass; 0 = choose              */
+    int32_t separate_passes; /* 0: a block's apply runs inside the next block's dot/Gram
+                                launch (one streaming launch per block); 1: separate
+                                dot/Gram and apply launches per block                 */
+    int32_t reserved;
 } cdgrab_options;
 
 /* Event-timed durations of the last cdgrab_balance_epoch call (timing >= 1);
@@ -49,10 +53,10 @@ typedef struct cdgrab_options {
 typedef struct cdgrab_timing {
     double generator_ms; /* time inside the generator callback's enqueued work */
     double balance_ms;   /* dot/Gram pass + reduce + resolve + apply pass, all blocks */
-    double pass1_ms;     /* dot/Gram pass, summed over blocks                  */
+    double pass1_ms;     /* dot/Gram launches (including the fused apply of the previous block) */
     double reduce_ms;    /* partial reduction                                  */
     double resolve_ms;   /* sequential sign resolution                         */
-    double pass2_ms;     /* apply pass                                         */
+    double pass2_ms;     /* stand-alone apply launches (only the last block's when fused) */
     double finish_ms;    /* permutation build + running-sum export             */
     int64_t blocks;      /* number of blocks processed                         */
     int32_t block_pairs; /* Bb used                                            */
@@ -70,8 +74,9 @@ typedef struct cdgrab_plan {
     int32_t pass1_groups;    /* workgroups of the dot/Gram pass                       */
     int32_t pass2_groups;    /* workgroups of the apply pass                          */
     int64_t workspace_bytes; /* running sum + partials (+ staging when streaming)     */
-    int64_t staging_bytes;   /* one staging block [Bb][2][d] fp32, 0 for dense input  */
-    double bytes_per_example;/* algorithmic HBM bytes per example: 8d + 12 d / Bb     */
+    int64_t staging_bytes;   /* two staging blocks [Bb][2][d] fp32, 0 for dense input */
+    double bytes_per_example;/* algorithmic HBM bytes per example: 8d + 8 d / Bb (each
+                                row twice, the running sum read and written per block) */
 } cdgrab_plan;
 
 /* Generator callback for streamed input ("grads-or-generator").  It must enqueue,

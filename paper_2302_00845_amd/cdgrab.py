@@ -31,7 +31,8 @@ class CdgrabError(RuntimeError):
 class _Options(ctypes.Structure):
     _fields_ = [("device", ctypes.c_int32), ("block_pairs", ctypes.c_int32),
                 ("stream", ctypes.c_void_p), ("timing", ctypes.c_int32),
-                ("pass1_groups", ctypes.c_int32)]
+                ("pass1_groups", ctypes.c_int32), ("separate_passes", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 class Timing(ctypes.Structure):
@@ -135,14 +136,16 @@ class Handle:
     """Owns a cdgrab_handle (workspace + stream binding) on one GPU."""
 
     def __init__(self, device: int = 0, block_pairs: int = 0, timing: int = 0,
-                 pass1_groups: int = 0, stream: Optional[torch.cuda.Stream] = None):
+                 pass1_groups: int = 0, stream: Optional[torch.cuda.Stream] = None,
+                 separate_passes: bool = False):
         self._lib = load_library()
         self.device = torch.device("cuda", device)
         if stream is None:
             stream = torch.cuda.current_stream(self.device)
         self.stream = stream
         opt = _Options(device=device, block_pairs=block_pairs, stream=stream.cuda_stream,
-                       timing=timing, pass1_groups=pass1_groups)
+                       timing=timing, pass1_groups=pass1_groups,
+                       separate_passes=1 if separate_passes else 0, reserved=0)
         h = ctypes.c_void_p()
         rc = self._lib.cdgrab_create(ctypes.byref(h), ctypes.byref(opt))
         if rc != CDGRAB_OK:

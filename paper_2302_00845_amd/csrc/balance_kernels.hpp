@@ -100,8 +100,20 @@ __device__ __forceinline__ void mfma_f64_16x16_coord(int lane, int v, int &i, in
 // (TE/4) w + 16 s + 4 kslot .. +3 (s = 0 .. TE/64-1) of the tile for pair `row`
 // of each 16-pair group.  TE = 128 halves the barriers per byte and is the
 // streaming configuration; TE = 64 gives short rows more workgroups.
-template <int BB, int VW, int TE>
-__global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const double *__restrict__ r_sum,
+//
+// With APPLY the same launch first applies the PREVIOUS block to the tile's slice
+// of the running sum (r += sum_k eps_k d_k over prev's rows, the work of pass 2):
+// every thread adds up the signed rows it loads, the RPI partial sums per element
+// are added in row order through LDS, the new slice is written back and is the one
+// the current block's dots are taken against.  The running sum is then read once
+// and written once per block, and a block costs one streaming launch instead of two.
+struct PrevBlock {
+    RowMap rm;           // rows of the previous block
+    const int8_t *eps;   // its resolved signs
+};
+
+template <int BB, int VW, int TE, bool APPLY>
+__global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, PrevBlock prev, double *__restrict__ r_sum,
                                                             double *__restrict__ partials,
                                                             int64_t ntiles)
 {
@@ -113,11 +125,13 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
     constexpr int STRIDE = TE + 4;            // floats per LDS row (16 B aligned, bank-skewed)
     constexpr int TILE_FLOATS = BB * STRIDE;
     constexpr int EPW = TE / kWaves;          // elements per wave per tile
-    // LDS: two stages of (first rows, second rows, running-sum chunk); the final
-    // cross-wave reduction reuses the same bytes.
+    // LDS: two stages of (first rows, second rows, running-sum chunk), with APPLY one
+    // buffer of RPI partial sums per element; the final cross-wave reduction reuses
+    // the same bytes.
     constexpr int STAGE_BYTES = 2 * TILE_FLOATS * 4 + TE * 8;
+    constexpr int APPLY_BYTES = APPLY ? RPI * TE * 8 : 0;
     constexpr int RED_BYTES = kWaves * (L::GRAM + RG * 64) * 8;
-    constexpr int SMEM = (2 * STAGE_BYTES > RED_BYTES) ? 2 * STAGE_BYTES : RED_BYTES;
+    constexpr int SMEM = (2 * STAGE_BYTES + APPLY_BYTES > RED_BYTES) ? 2 * STAGE_BYTES + APPLY_BYTES : RED_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
 
     const int tid = threadIdx.x;
@@ -128,6 +142,8 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
     const int lrow = tid / TPR;
     const int chunk = tid % TPR;
     const float *src[LOADS];
+    const float *psrc[APPLY ? LOADS : 1];
+    float psign[APPLY ? LOADS : 1];
     int lds_off[LOADS];
 #pragma unroll
     for (int u = 0; u < LOADS; ++u) {
@@ -135,6 +151,12 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
         int j = rr >> 1, which = rr & 1;
         src[u] = (j < rm.nb) ? rm.row(j, which) : nullptr;
         lds_off[u] = (which * TILE_FLOATS + j * STRIDE + chunk * 4) * 4;
+        if constexpr (APPLY) {
+            const bool have = j < prev.rm.nb;
+            psrc[u] = have ? prev.rm.row(j, which) : nullptr;
+            // d_k = second - first, so the second row enters with eps and the first with -eps
+            psign[u] = have ? (float)prev.eps[j] * (which ? 1.0f : -1.0f) : 0.0f;
+        }
     }
 
     double4_t acc[L::NT];
@@ -148,12 +170,17 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
     const int kslot = lane >> 4;
 
     float4 stage_regs[LOADS];
+    float4 prev_regs[APPLY ? LOADS : 1];
     double2 stage_s = make_double2(0.0, 0.0);
 
     int64_t tile = blockIdx.x;
     if (tile < ntiles) {
 #pragma unroll
         for (int u = 0; u < LOADS; ++u) stage_regs[u] = load4<VW>(src[u], tile * TE + chunk * 4, d);
+        if constexpr (APPLY) {
+#pragma unroll
+            for (int u = 0; u < LOADS; ++u) prev_regs[u] = load4<VW>(psrc[u], tile * TE + chunk * 4, d);
+        }
         if (tid < TE / 2) stage_s = *reinterpret_cast<const double2 *>(r_sum + tile * TE + tid * 2);
     }
     int buf = 0;
@@ -162,6 +189,31 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
 #pragma unroll
         for (int u = 0; u < LOADS; ++u)
             *reinterpret_cast<float4 *>(stage + lds_off[u]) = stage_regs[u];
+        if constexpr (APPLY) {
+            // this thread's signed sum of the previous block's rows it holds
+            double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+#pragma unroll
+            for (int u = 0; u < LOADS; ++u) {
+                const double sg = (double)psign[u];
+                a0 = __builtin_fma(sg, (double)prev_regs[u].x, a0);
+                a1 = __builtin_fma(sg, (double)prev_regs[u].y, a1);
+                a2 = __builtin_fma(sg, (double)prev_regs[u].z, a2);
+                a3 = __builtin_fma(sg, (double)prev_regs[u].w, a3);
+            }
+            double *ap = reinterpret_cast<double *>(smem + 2 * STAGE_BYTES) + lrow * TE + chunk * 4;
+            *reinterpret_cast<double2 *>(ap) = make_double2(a0, a1);
+            *reinterpret_cast<double2 *>(ap + 2) = make_double2(a2, a3);
+            __syncthreads();
+            if (tid < TE / 2) {
+                const double *col = reinterpret_cast<const double *>(smem + 2 * STAGE_BYTES) + tid * 2;
+                double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+                for (int q = 0; q < RPI; ++q) { s0 += col[q * TE]; s1 += col[q * TE + 1]; }
+                stage_s.x += s0;
+                stage_s.y += s1;
+                *reinterpret_cast<double2 *>(r_sum + tile * TE + tid * 2) = stage_s;
+            }
+        }
         if (tid < TE / 2)
             *reinterpret_cast<double2 *>(stage + 2 * TILE_FLOATS * 4 + tid * 16) = stage_s;
         __syncthreads();
@@ -171,6 +223,10 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, const dou
         if (nxt < ntiles) {
 #pragma unroll
             for (int u = 0; u < LOADS; ++u) stage_regs[u] = load4<VW>(src[u], nxt * TE + chunk * 4, d);
+            if constexpr (APPLY) {
+#pragma unroll
+                for (int u = 0; u < LOADS; ++u) prev_regs[u] = load4<VW>(psrc[u], nxt * TE + chunk * 4, d);
+            }
             if (tid < TE / 2) stage_s = *reinterpret_cast<const double2 *>(r_sum + nxt * TE + tid * 2);
         }
 

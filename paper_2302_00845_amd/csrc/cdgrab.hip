@@ -38,6 +38,7 @@ struct cdgrab_handle {
     int block_pairs_opt = 0;
     int timing = 0;
     int pass1_groups_opt = 0;
+    int separate_passes = 0;
     int num_cu = 256;
     std::string err;
 
@@ -50,7 +51,7 @@ struct cdgrab_handle {
     float *zero_row = nullptr; int64_t zero_row_cap = 0;  // a zero vector standing in for a missing stale mean
     float *train_delta = nullptr; int64_t train_delta_cap = 0;  // [m][classes] softmax deltas of one step
     double *herd_ws = nullptr; int64_t herd_cap = 0;      // herding evaluator: segment sums, starts, mean
-    float *staging = nullptr;  int64_t staging_cap = 0;   // floats
+    float *staging = nullptr;  int64_t staging_cap = 0;   // floats: two staging chunks (the fused pass reads the previous block too)
 
     std::vector<hipEvent_t> event_pool;
     std::vector<Mark> marks;
@@ -117,11 +118,12 @@ int plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs, int32_t str
                                         : (int64_t)num_cu * (plan->tile_elems == 128 ? 2 : 4);
     plan->pass1_groups = (int32_t)std::max<int64_t>(1, std::min<int64_t>(want, ntiles));
     plan->pass2_groups = (int32_t)((d + kThreads * 4 - 1) / (kThreads * 4));
-    plan->staging_bytes = streamed ? (int64_t)plan->block_pairs * 2 * d * 4 : 0;
+    // two staging blocks: the fused launch reads the previous block's rows as well
+    plan->staging_bytes = streamed ? 2 * (int64_t)plan->block_pairs * 2 * d * 4 : 0;
     plan->workspace_bytes = round_up(d, kPadE) * 8 +
                             (int64_t)plan->pass1_groups * part_size(plan->block_pairs) * 8 +
                             plan->staging_bytes;
-    plan->bytes_per_example = 8.0 * (double)d + 12.0 * (double)d / plan->block_pairs;
+    plan->bytes_per_example = 8.0 * (double)d + 8.0 * (double)d / plan->block_pairs;
     return CDGRAB_OK;
 }
 
@@ -162,15 +164,28 @@ int ensure(cdgrab_handle *h, T *&ptr, int64_t &cap, int64_t want) {
 }
 
 template <int BB, int VW>
-void launch_pass1(cdgrab_handle *h, const RowMap &rm, const cdgrab_plan &plan) {
+void launch_pass1(cdgrab_handle *h, const RowMap &rm, const PrevBlock *prev, const cdgrab_plan &plan) {
+    PrevBlock none;
+    none.rm = rm;
+    none.rm.nb = 0;
+    none.eps = h->eps_blk;
+    const dim3 grid(plan.pass1_groups), block(kThreads);
     if (plan.tile_elems == 128) {
         int64_t ntiles = (rm.d + 127) / 128;
-        hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 128>), dim3(plan.pass1_groups), dim3(kThreads), 0,
-                           h->stream, rm, h->r_sum, h->partials, ntiles);
+        if (prev)
+            hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 128, true>), grid, block, 0, h->stream, rm, *prev,
+                               h->r_sum, h->partials, ntiles);
+        else
+            hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 128, false>), grid, block, 0, h->stream, rm, none,
+                               h->r_sum, h->partials, ntiles);
     } else {
         int64_t ntiles = (rm.d + 63) / 64;
-        hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 64>), dim3(plan.pass1_groups), dim3(kThreads), 0,
-                           h->stream, rm, h->r_sum, h->partials, ntiles);
+        if (prev)
+            hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 64, true>), grid, block, 0, h->stream, rm, *prev,
+                               h->r_sum, h->partials, ntiles);
+        else
+            hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 64, false>), grid, block, 0, h->stream, rm, none,
+                               h->r_sum, h->partials, ntiles);
     }
 }
 template <int BB, int VW>
@@ -199,15 +214,18 @@ void launch_resolve(cdgrab_handle *h, const RowMap &rm, int8_t *signs_out, doubl
                        rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out, h->uniforms);
 }
 
+// One block: dots + Gram (with the previous block applied in the same launch when
+// `prev` is given), reduction, sign resolution, and -- unless the apply is left to the
+// next block's launch -- the apply pass.
 template <int BB>
-int run_block_vw(cdgrab_handle *h, const RowMap &rm, const cdgrab_plan &plan, int8_t *signs_out,
-                 double *dots_out) {
+int run_block_vw(cdgrab_handle *h, const RowMap &rm, const PrevBlock *prev, bool apply_now,
+                 const cdgrab_plan &plan, int8_t *signs_out, double *dots_out) {
     const int part = PartLayout<BB>::PART;
     MARK(h, 2, kPass1);
     switch (plan.vector_width) {
-        case 4: launch_pass1<BB, 4>(h, rm, plan); break;
-        case 2: launch_pass1<BB, 2>(h, rm, plan); break;
-        default: launch_pass1<BB, 1>(h, rm, plan); break;
+        case 4: launch_pass1<BB, 4>(h, rm, prev, plan); break;
+        case 2: launch_pass1<BB, 2>(h, rm, prev, plan); break;
+        default: launch_pass1<BB, 1>(h, rm, prev, plan); break;
     }
     MARK(h, 2, kReduce);
     hipLaunchKernelGGL(reduce_partials,
@@ -215,6 +233,20 @@ int run_block_vw(cdgrab_handle *h, const RowMap &rm, const cdgrab_plan &plan, in
                        dim3(kThreads), 0, h->stream, h->partials, h->reduced, part, plan.pass1_groups);
     MARK(h, 2, kResolve);
     launch_resolve<BB>(h, rm, signs_out, dots_out);
+    if (apply_now) {
+        MARK(h, 2, kPass2);
+        switch (plan.vector_width) {
+            case 4: launch_pass2<BB, 4>(h, rm, plan.pass2_groups); break;
+            case 2: launch_pass2<BB, 2>(h, rm, plan.pass2_groups); break;
+            default: launch_pass2<BB, 1>(h, rm, plan.pass2_groups); break;
+        }
+    }
+    HIP_TRY(h, hipGetLastError());
+    return CDGRAB_OK;
+}
+
+template <int BB>
+int apply_block_vw(cdgrab_handle *h, const RowMap &rm, const cdgrab_plan &plan) {
     MARK(h, 2, kPass2);
     switch (plan.vector_width) {
         case 4: launch_pass2<BB, 4>(h, rm, plan.pass2_groups); break;
@@ -251,6 +283,7 @@ int cdgrab_create(cdgrab_handle **out, const cdgrab_options *opt) {
     h->block_pairs_opt = o.block_pairs;
     h->timing = o.timing;
     h->pass1_groups_opt = o.pass1_groups;
+    h->separate_passes = o.separate_passes ? 1 : 0;
     hipDeviceProp_t prop;
     if (hipSetDevice(h->device) == hipSuccess && hipGetDeviceProperties(&prop, h->device) == hipSuccess)
         h->num_cu = prop.multiProcessorCount;
@@ -348,7 +381,9 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)kReduceSlices * PartLayout<64>::PART); if (rc) return rc; }
     if (!h->eps_blk) { fixed_cap = 0; rc = ensure(h, h->eps_blk, fixed_cap, (int64_t)64); if (rc) return rc; }
     if (chunk_pairs <= 0) chunk_pairs = bb;
-    if (streamed) { rc = ensure(h, h->staging, h->staging_cap, chunk_pairs * 2 * d); if (rc) return rc; }
+    const bool fused = !h->separate_passes;
+    const int64_t staging_chunk = chunk_pairs * 2 * d;  // floats per staging chunk
+    if (streamed) { rc = ensure(h, h->staging, h->staging_cap, (fused ? 2 : 1) * staging_chunk); if (rc) return rc; }
 
     h->marks.clear();
     h->events_used = 0;
@@ -362,11 +397,17 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     rm.base = grads;
     for (int64_t &o : rm.off) o = 0;
     const int64_t chunk = streamed ? chunk_pairs : plan.pairs;
-    for (int64_t first = 0; first < plan.pairs; first += chunk) {
+    PrevBlock prev;
+    prev.eps = h->eps_blk;
+    bool have_prev = false;
+    int64_t chunk_index = 0;
+    for (int64_t first = 0; first < plan.pairs; first += chunk, ++chunk_index) {
         const int64_t cnt = std::min<int64_t>(chunk, plan.pairs - first);
+        // with the fused pass the previous block's rows must outlive this chunk's staging
+        float *stage_buf = h->staging + ((fused && (chunk_index & 1)) ? staging_chunk : 0);
         if (streamed) {
             MARK(h, 1, kGen);
-            int grc = gen(gen_ctx, first, cnt, h->staging, h->stream);
+            int grc = gen(gen_ctx, first, cnt, stage_buf, h->stream);
             if (grc != 0)
                 return fail(h, CDGRAB_EGEN, "generator callback returned %d at pair %lld", grc,
                             (long long)first);
@@ -375,7 +416,7 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
             rm.k0 = p0 / m;
             rm.i0 = (int32_t)(p0 - rm.k0 * m);
             rm.nb = (int32_t)std::min<int64_t>(bb, first + cnt - p0);
-            if (streamed) rm.base = h->staging + (p0 - first) * 2 * d;
+            if (streamed) rm.base = stage_buf + (p0 - first) * 2 * d;
             for (int j = 0; j < rm.nb; ++j) {
                 if (streamed) {
                     rm.off[2 * j] = (int64_t)(2 * j) * d;
@@ -391,11 +432,21 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                 rm.off[2 * j + 1] = rm.off[2 * j] + d;
             }
             MARK(h, 1, kBalance);
-            rc = (bb == 64)   ? run_block_vw<64>(h, rm, plan, signs_out, dots_out)
-                 : (bb == 32) ? run_block_vw<32>(h, rm, plan, signs_out, dots_out)
-                              : run_block_vw<16>(h, rm, plan, signs_out, dots_out);
+            const PrevBlock *pp = (fused && have_prev) ? &prev : nullptr;
+            rc = (bb == 64)   ? run_block_vw<64>(h, rm, pp, !fused, plan, signs_out, dots_out)
+                 : (bb == 32) ? run_block_vw<32>(h, rm, pp, !fused, plan, signs_out, dots_out)
+                              : run_block_vw<16>(h, rm, pp, !fused, plan, signs_out, dots_out);
             if (rc) return rc;
+            prev.rm = rm;
+            have_prev = true;
         }
+    }
+    if (fused && have_prev) {  // the last block has no successor to apply it
+        MARK(h, 1, kBalance);
+        rc = (bb == 64)   ? apply_block_vw<64>(h, prev.rm, plan)
+             : (bb == 32) ? apply_block_vw<32>(h, prev.rm, plan)
+                          : apply_block_vw<16>(h, prev.rm, plan);
+        if (rc) return rc;
     }
     MARK(h, 1, kFinish);
     {
