@@ -40,8 +40,9 @@ def parse_args():
     ap.add_argument("--workload", default="c4_resnet18")
     ap.add_argument("--block-pairs", type=int, default=0)
     ap.add_argument("--pass1-groups", type=int, default=0)
-    ap.add_argument("--separate-passes", action="store_true",
-                    help="separate dot/Gram and apply launches per block instead of the fused launch")
+    ap.add_argument("--apply-mode", type=int, default=0,
+                    help="0: library's choice by row length; 1: separate apply launch per block; "
+                         "2: apply fused into the next block's dot/Gram launch")
     ap.add_argument("--n", type=int, default=0, help="override rows per worker (shorter epoch)")
     ap.add_argument("--seed", type=int, default=2302)
     ap.add_argument("--cpu-sample-pairs", type=int, default=-1,
@@ -164,6 +165,7 @@ def main():
         return bench_next_rows(args)
     w = workloads.CONFIGS[args.workload]
     m, n, d = w.m, (args.n or w.n), w.d
+    fused = args.apply_mode == 2 or (args.apply_mode == 0 and bool(pkg.cdgrab_plan_epoch(m, n, d)["fused_apply"]))
     N = m * n
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
@@ -173,7 +175,7 @@ def main():
     gen_fn = gen_ctx = grads = rows_src = None
     pergrad_ms = None
     h = pkg.Handle(device=0, block_pairs=args.block_pairs, timing=1, pass1_groups=args.pass1_groups,
-                   separate_passes=args.separate_passes)
+                   apply_mode=args.apply_mode)
     if w.kind == "stream":
         rows_src = synth.from_workload(w, args.seed, n=n)
         gen_fn, gen_ctx = rows_src.device_callback(str(dev))
@@ -231,14 +233,14 @@ def main():
     kernels = {}
     if not args.no_profile_step:
         hp = pkg.Handle(device=0, block_pairs=args.block_pairs, timing=2, pass1_groups=args.pass1_groups,
-                        separate_passes=args.separate_passes)
+                        apply_mode=args.apply_mode)
         if w.kind == "softmax":
             pkg.cdgrab_pergrad(hp, Xd, yd, Wd, G)
         pkg.cdgrab_balance_epoch(hp, m, n, d, grads=grads, gen=gen_fn, gen_ctx=gen_ctx, perm_in=perm_in)
         tp = hp.timing()
         pairs = N // 2
         avg_pairs = pairs / blocks
-        if args.separate_passes:
+        if not fused:
             # algorithmic bytes per launch: both rows of every pair in the block (fp32) plus the
             # double running sum (read in pass 1; read and written in pass 2)
             per_kernel = (("pass1_dots_gram", tp["pass1_ms"], 8.0 * avg_pairs * d + 8.0 * d),
@@ -272,7 +274,7 @@ def main():
         roofline["frac_of_plain_read"] = roofline["achieved"] / read_ceiling
     # whole balancer against the roofline: 8d + 12 d / Bb bytes per example with separate passes
     # (running sum read twice, written once per block), 8d + 8 d / Bb with the fused launch
-    bytes_per_example = 8.0 * d + (12.0 if args.separate_passes else 8.0) * d / bb
+    bytes_per_example = 8.0 * d + (8.0 if fused else 12.0) * d / bb
     balancer_gbs = bytes_per_example * N / (path_ms * 1e-3) / 1e9
 
     # the same epoch without the generator's cache drain (its write-back then lands in pass 1)
@@ -345,7 +347,7 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": args.workload, "m": m, "n": n, "d": d, "examples": N,
                    "block_pairs": bb, "blocks": blocks, "input": w.kind,
-                   "fused_apply": not args.separate_passes,
+                   "fused_apply": fused,
                    "input_drain": bool(w.kind == "stream" and not args.no_input_drain),
                    "rows_dtype": "f32", "parallelism": "1 GPU, m workers as a batch axis"},
         "generator_ms_per_step": gen_ms, "wall_ms_per_step": wall_ms,

@@ -42,9 +42,10 @@ typedef struct cdgrab_options {
     int32_t timing;      /* 0 off; 1 record events around generator / balancer work;
                             2 additionally around every balancer kernel               */
     int32_t pass1_groups; /* workgroups of the dot/Gram pass; 0 = choose              */
-    int32_t separate_passes; /* 0: a block's apply runs inside the next block's dot/Gram
-                                launch (one streaming launch per block); 1: separate
-                                dot/Gram and apply launches per block                 */
+    int32_t apply_mode;  /* how r += sum eps_k d_k of a block is launched: 1 = its own
+                            apply launch after the block is resolved; 2 = inside the next
+                            block's dot/Gram launch (one streaming launch per block, the
+                            running sum read once per block); 0 = choose by row length  */
     int32_t reserved;
 } cdgrab_options;
 
@@ -70,13 +71,14 @@ typedef struct cdgrab_plan {
     int32_t block_pairs;     /* Bb                                                    */
     int32_t vector_width;    /* fp32 elements per global load: 4, 2 or 1              */
     int32_t tile_elems;      /* elements of d per LDS tile of the dot/Gram pass        */
-    int32_t reserved;
+    int32_t fused_apply;     /* 1: apply fused into the next block's launch (apply_mode 0) */
     int32_t pass1_groups;    /* workgroups of the dot/Gram pass                       */
     int32_t pass2_groups;    /* workgroups of the apply pass                          */
     int64_t workspace_bytes; /* running sum + partials (+ staging when streaming)     */
-    int64_t staging_bytes;   /* two staging blocks [Bb][2][d] fp32, 0 for dense input */
-    double bytes_per_example;/* algorithmic HBM bytes per example: 8d + 8 d / Bb (each
-                                row twice, the running sum read and written per block) */
+    int64_t staging_bytes;   /* staging blocks [Bb][2][d] fp32 (two when fused), 0 for dense input */
+    double bytes_per_example;/* algorithmic HBM bytes per example: each row twice, plus the
+                                double running sum per block: 8d + 12 d / Bb (read twice,
+                                written once) or 8d + 8 d / Bb when fused               */
 } cdgrab_plan;
 
 /* Generator callback for streamed input ("grads-or-generator").  It must enqueue,

@@ -38,7 +38,7 @@ struct cdgrab_handle {
     int block_pairs_opt = 0;
     int timing = 0;
     int pass1_groups_opt = 0;
-    int separate_passes = 0;
+    int apply_mode = 0;  // 0 choose by row length, 1 separate apply launch, 2 apply fused into the next block's launch
     int num_cu = 256;
     std::string err;
 
@@ -96,6 +96,12 @@ int pick_block_pairs(int64_t pairs, int64_t d, int32_t requested) {
     return 32;
 }
 
+// Measured on MI355X: applying a block inside the next block's dot/Gram launch wins up
+// to about 3M elements per row (one launch and one read of the running sum less: 7 % at
+// 1M, 15 % at 8K); beyond that the heavier fused kernel streams 4-10 % slower than the
+// two lean ones.
+bool fuse_apply_by_default(int64_t d) { return d <= ((int64_t)1 << 21); }
+
 int part_size(int bb) {
     return bb == 64 ? PartLayout<64>::PART : bb == 32 ? PartLayout<32>::PART : PartLayout<16>::PART;
 }
@@ -118,12 +124,14 @@ int plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs, int32_t str
                                         : (int64_t)num_cu * (plan->tile_elems == 128 ? 2 : 4);
     plan->pass1_groups = (int32_t)std::max<int64_t>(1, std::min<int64_t>(want, ntiles));
     plan->pass2_groups = (int32_t)((d + kThreads * 4 - 1) / (kThreads * 4));
-    // two staging blocks: the fused launch reads the previous block's rows as well
-    plan->staging_bytes = streamed ? 2 * (int64_t)plan->block_pairs * 2 * d * 4 : 0;
+    // with the fused launch two staging blocks: it reads the previous block's rows as well
+    const bool fused = fuse_apply_by_default(d);
+    plan->fused_apply = fused ? 1 : 0;
+    plan->staging_bytes = streamed ? (fused ? 2 : 1) * (int64_t)plan->block_pairs * 2 * d * 4 : 0;
     plan->workspace_bytes = round_up(d, kPadE) * 8 +
                             (int64_t)plan->pass1_groups * part_size(plan->block_pairs) * 8 +
                             plan->staging_bytes;
-    plan->bytes_per_example = 8.0 * (double)d + 8.0 * (double)d / plan->block_pairs;
+    plan->bytes_per_example = 8.0 * (double)d + (fused ? 8.0 : 12.0) * (double)d / plan->block_pairs;
     return CDGRAB_OK;
 }
 
@@ -271,6 +279,7 @@ int cdgrab_create(cdgrab_handle **out, const cdgrab_options *opt) {
     if (o.timing < 0 || o.timing > 2) return fail(nullptr, CDGRAB_EINVAL, "timing must be 0, 1 or 2");
     if (o.pass1_groups < 0 || o.pass1_groups > 65536)
         return fail(nullptr, CDGRAB_EINVAL, "pass1_groups out of range");
+    if (o.apply_mode < 0 || o.apply_mode > 2) return fail(nullptr, CDGRAB_EINVAL, "apply_mode must be 0, 1 or 2");
     int count = 0;
     hipError_t e = hipGetDeviceCount(&count);
     if (e != hipSuccess || o.device < 0 || o.device >= count)
@@ -283,7 +292,7 @@ int cdgrab_create(cdgrab_handle **out, const cdgrab_options *opt) {
     h->block_pairs_opt = o.block_pairs;
     h->timing = o.timing;
     h->pass1_groups_opt = o.pass1_groups;
-    h->separate_passes = o.separate_passes ? 1 : 0;
+    h->apply_mode = o.apply_mode;
     hipDeviceProp_t prop;
     if (hipSetDevice(h->device) == hipSuccess && hipGetDeviceProperties(&prop, h->device) == hipSuccess)
         h->num_cu = prop.multiProcessorCount;
@@ -381,7 +390,7 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)kReduceSlices * PartLayout<64>::PART); if (rc) return rc; }
     if (!h->eps_blk) { fixed_cap = 0; rc = ensure(h, h->eps_blk, fixed_cap, (int64_t)64); if (rc) return rc; }
     if (chunk_pairs <= 0) chunk_pairs = bb;
-    const bool fused = !h->separate_passes;
+    const bool fused = h->apply_mode == 2 || (h->apply_mode == 0 && fuse_apply_by_default(d));
     const int64_t staging_chunk = chunk_pairs * 2 * d;  // floats per staging chunk
     if (streamed) { rc = ensure(h, h->staging, h->staging_cap, (fused ? 2 : 1) * staging_chunk); if (rc) return rc; }
 

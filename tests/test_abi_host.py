@@ -55,8 +55,11 @@ def test_plan_epoch_headline_shapes(p):
     c4 = p.cdgrab_plan_epoch(32, 512, 11_200_000, streamed=True)
     assert c4["pairs"] == 8192 and c4["block_pairs"] == 32 and c4["blocks"] == 256
     assert c4["vector_width"] == 4
-    assert c4["staging_bytes"] == 2 * 32 * 2 * 11_200_000 * 4
-    assert c4["bytes_per_example"] == 8 * 11_200_000 + 8 * 11_200_000 / 32
+    assert c4["staging_bytes"] == 32 * 2 * 11_200_000 * 4 and c4["fused_apply"] == 0
+    assert c4["bytes_per_example"] == 8 * 11_200_000 + 12 * 11_200_000 / 32
+    c3 = p.cdgrab_plan_epoch(32, 1024, 1 << 20, streamed=True)
+    assert c3["fused_apply"] == 1 and c3["staging_bytes"] == 2 * 32 * 2 * (1 << 20) * 4
+    assert c3["bytes_per_example"] == 8 * (1 << 20) + 8 * (1 << 20) / 32
     c2 = p.cdgrab_plan_epoch(16, 3750, 7850)
     assert c2["pairs"] == 30000 and c2["block_pairs"] == 64 and c2["blocks"] == 469 and c2["vector_width"] == 2
     assert c2["staging_bytes"] == 0

@@ -21,9 +21,9 @@ def lib():
     return p
 
 
-def run_epoch(p, z, perm_in=None, block_pairs=0, pass1_groups=0, separate_passes=False):
+def run_epoch(p, z, perm_in=None, block_pairs=0, pass1_groups=0, apply_mode=0):
     m, n, d = z.shape
-    h = p.Handle(block_pairs=block_pairs, pass1_groups=pass1_groups, separate_passes=separate_passes)
+    h = p.Handle(block_pairs=block_pairs, pass1_groups=pass1_groups, apply_mode=apply_mode)
     zt = torch.from_numpy(z).cuda()
     pt = torch.from_numpy(perm_in).cuda() if perm_in is not None else None
     out = p.cdgrab_balance_epoch(h, m, n, d, grads=zt, perm_in=pt, want_r32=True, want_r64=True,
@@ -84,14 +84,14 @@ def test_fused_and_separate_passes_agree(lib, m, n, d, bb):
     its own launch are the same computation: bit-identical on exact input, and both
     within the oracle's tolerances on heavy-tailed rows."""
     zi = workloads.integer_rows(m + n, m, n, d, 6)
-    a = run_epoch(lib, zi, block_pairs=bb, separate_passes=False)
-    b = run_epoch(lib, zi, block_pairs=bb, separate_passes=True)
+    a = run_epoch(lib, zi, block_pairs=bb, apply_mode=2)
+    b = run_epoch(lib, zi, block_pairs=bb, apply_mode=1)
     for k in ("signs", "perm", "r64", "dots"):
         assert np.array_equal(a[k], b[k]), k
     check_epoch(zi, a, expect_exact_signs=True)
     z = workloads.heavy_rows(m * n, m, n, d)
-    check_epoch(z, run_epoch(lib, z, block_pairs=bb, separate_passes=False))
-    check_epoch(z, run_epoch(lib, z, block_pairs=bb, separate_passes=True))
+    check_epoch(z, run_epoch(lib, z, block_pairs=bb, apply_mode=2))
+    check_epoch(z, run_epoch(lib, z, block_pairs=bb, apply_mode=1))
 
 
 def test_unaligned_base_pointer(lib):
