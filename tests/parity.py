@@ -1,7 +1,7 @@
 """Shared helpers of the GPU parity tests: compare the HIP path's outputs with
 the CPU oracle on the same rows.
 
-Tolerances (from the benchmark spec):
+Tolerances:
   * permutations: bit-exact given the signs;
   * signs: identical wherever |<r,d>| > 1e-9 * ||r|| * ||d||.  Inside that margin
     either sign is a correct outcome of the greedy rule in finite precision; the
