@@ -334,36 +334,47 @@ __global__ __launch_bounds__(kThreads) void reduce_partials(const double *__rest
 }
 
 // ---------------------------------------------------------------------------
-// Sequential sign resolution.  All 256 threads finish the reduction and unpack
+// Sequential sign resolution.  All threads of the workgroup finish the reduction and unpack
 // the Gram tiles into LDS; then one wavefront walks the block: lane k carries
 // t_k = <r, d_k> + sum_{j<k, decided} eps_j G[j][k]; step j broadcasts t_j,
 // fixes eps_j = +1 if t_j <= 0 else -1 (or, given uniform draws, the randomized
 // rule) and updates the later lanes.
+constexpr int kResolveThreads = 1024;
+
 template <int BB>
-__global__ __launch_bounds__(kThreads) void resolve_signs(const double *__restrict__ sliced, int nb,
-                                                          int64_t k0, int32_t i0, int32_t m, int64_t half_n,
-                                                          int8_t *__restrict__ eps_blk,
-                                                          int8_t *__restrict__ signs_out,
-                                                          double *__restrict__ dots_out,
-                                                          const float *__restrict__ uniforms)
+__global__ __launch_bounds__(kResolveThreads) void resolve_signs(const double *__restrict__ sliced, int nb,
+                                                                 int64_t k0, int32_t i0, int32_t m, int64_t half_n,
+                                                                 int8_t *__restrict__ eps_blk,
+                                                                 int8_t *__restrict__ signs_out,
+                                                                 double *__restrict__ dots_out,
+                                                                 const float *__restrict__ uniforms)
 {
     using L = PartLayout<BB>;
     __shared__ double G[BB][BB + 1];
     __shared__ double P[BB];
-    for (int idx = threadIdx.x; idx < L::PART; idx += kThreads) {
-        double val = 0.0;
+    // two consecutive entries per thread and step (16 B loads); GRAM and PART are even
+    for (int idx = 2 * threadIdx.x; idx < L::PART; idx += 2 * kResolveThreads) {
+        double2 val = make_double2(0.0, 0.0);
 #pragma unroll
-        for (int s = 0; s < kReduceSlices; ++s) val += sliced[(int64_t)s * L::PART + idx];
-        if (idx >= L::GRAM) { P[idx - L::GRAM] = val; continue; }
-        int tile = idx >> 8, v = (idx >> 6) & 3, ln = idx & 63;
-        int i, j;
-        mfma_f64_16x16_coord(ln, v, i, j);
+        for (int s = 0; s < kReduceSlices; ++s) {
+            const double2 v = *reinterpret_cast<const double2 *>(sliced + (int64_t)s * L::PART + idx);
+            val.x += v.x;
+            val.y += v.y;
+        }
+        if (idx >= L::GRAM) { P[idx - L::GRAM] = val.x; P[idx - L::GRAM + 1] = val.y; continue; }
+        const int tile = idx >> 8, v = (idx >> 6) & 3, ln = idx & 63;
         // tiles are stored row group by row group, upper triangle only: (0,0), (0,1), .., (1,1), ..
         int tg = 0, th = tile;
         while (th >= L::RG - tg) { th -= L::RG - tg; ++tg; }
         th += tg;
-        G[16 * tg + i][16 * th + j] = val;
-        if (th != tg) G[16 * th + j][16 * tg + i] = val;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            int i, j;
+            mfma_f64_16x16_coord(ln + q, v, i, j);
+            const double x = q ? val.y : val.x;
+            G[16 * tg + i][16 * th + j] = x;
+            if (th != tg) G[16 * th + j][16 * tg + i] = x;
+        }
     }
     __syncthreads();
     if (threadIdx.x >= 64) return;
