@@ -335,13 +335,27 @@ int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
                     (long long)N, (long long)in_dim, (long long)classes);
     if (N == 0) return CDGRAB_OK;
     if (!X || !y || !W || !G_out) return fail(h, CDGRAB_EINVAL, "cdgrab_pergrad: null pointer");
-    size_t lds = (size_t)kGradWaves * (size_t)(in_dim + 1 + classes) * sizeof(float);
-    if (lds > 64 * 1024)
+    const size_t lds_waves = (size_t)kGradWaves * (size_t)(in_dim + 1 + classes) * sizeof(float);
+    if (lds_waves > 64 * 1024)
         return fail(h, CDGRAB_EINVAL, "cdgrab_pergrad: in_dim + classes too large for LDS staging");
     HIP_TRY(h, hipSetDevice(h->device));
+    // weights in LDS when they fit beside the per-wave staging (64 KB per workgroup)
+    const int wstride = (int)classes | 1;
+    const size_t lds_w = (size_t)(in_dim + 1) * (size_t)wstride * sizeof(float);
+    const bool wlds = lds_waves + lds_w <= 64 * 1024;
+    const size_t lds = lds_waves + (wlds ? lds_w : 0);
+    // each wavefront loops over examples: as many workgroups as stay resident
+    int64_t per_cu = (int64_t)((160 * 1024) / lds);
+    if (per_cu > 8) per_cu = 8;
+    if (per_cu < 1) per_cu = 1;
     int64_t groups = (N + kGradWaves - 1) / kGradWaves;
-    hipLaunchKernelGGL(softmax_pergrad, dim3((unsigned)groups), dim3(kGradWaves * 64), lds, h->stream, X,
-                       y, W, G_out, N, (int)in_dim, (int)classes);
+    if (groups > per_cu * h->num_cu) groups = per_cu * h->num_cu;
+    if (wlds)
+        hipLaunchKernelGGL(softmax_pergrad<true>, dim3((unsigned)groups), dim3(kGradWaves * 64), lds, h->stream,
+                           X, y, W, G_out, N, (int)in_dim, (int)classes, wstride);
+    else
+        hipLaunchKernelGGL(softmax_pergrad<false>, dim3((unsigned)groups), dim3(kGradWaves * 64), lds,
+                           h->stream, X, y, W, G_out, N, (int)in_dim, (int)classes, (int)classes);
     HIP_TRY(h, hipGetLastError());
     return CDGRAB_OK;
 }
@@ -635,21 +649,32 @@ int cdgrab_herding_bound(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
     HerdingShape sh;
     sh.m = m; sh.n = n; sh.d = d;
     // enough (segment, element) threads to fill the chip, at least one step per segment
+    const int64_t quads = (d + 3) / 4;
     int64_t want_threads = (int64_t)h->num_cu * 2048;
-    int64_t segs = std::max<int64_t>(1, std::min<int64_t>(n, (want_threads + d - 1) / d));
+    int64_t segs = std::max<int64_t>(1, std::min<int64_t>(n, (want_threads + quads - 1) / quads));
     sh.seg_len = (n + segs - 1) / segs;
     sh.segments = (n + sh.seg_len - 1) / sh.seg_len;
     int rc = ensure(h, h->herd_ws, h->herd_cap, 2 * sh.segments * d + d);
     if (rc) return rc;
     double *segsum = h->herd_ws, *start = segsum + sh.segments * d, *zbar = start + sh.segments * d;
-    const int64_t threads = sh.segments * d;
+    const int64_t threads = sh.segments * quads;
     const unsigned grid = (unsigned)((threads + 255) / 256);
     unsigned long long *bits = reinterpret_cast<unsigned long long *>(bound_out);
+    // widest load every row start allows
+    const uintptr_t zb = reinterpret_cast<uintptr_t>(z);
+    const int vw = (d % 4 == 0 && zb % 16 == 0) ? 4 : (d % 2 == 0 && zb % 8 == 0) ? 2 : 1;
     hipLaunchKernelGGL(herding_clear, dim3(1), dim3(1), 0, h->stream, bits);
-    hipLaunchKernelGGL(herding_segment_sums, dim3(grid), dim3(256), 0, h->stream, z, perm, sh, segsum);
-    hipLaunchKernelGGL(herding_segment_offsets, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, h->stream,
-                       segsum, sh, zbar, start);
-    hipLaunchKernelGGL(herding_prefix_max, dim3(grid), dim3(256), 0, h->stream, z, perm, sh, zbar, start, bits);
+    auto launch = [&](auto vw_tag) {
+        constexpr int VW = decltype(vw_tag)::value;
+        hipLaunchKernelGGL((herding_segment_sums<VW>), dim3(grid), dim3(256), 0, h->stream, z, perm, sh, segsum);
+        hipLaunchKernelGGL(herding_segment_offsets, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, h->stream,
+                           segsum, sh, zbar, start);
+        hipLaunchKernelGGL((herding_prefix_max<VW>), dim3(grid), dim3(256), 0, h->stream, z, perm, sh, zbar, start,
+                           bits);
+    };
+    if (vw == 4) launch(std::integral_constant<int, 4>{});
+    else if (vw == 2) launch(std::integral_constant<int, 2>{});
+    else launch(std::integral_constant<int, 1>{});
     HIP_TRY(h, hipGetLastError());
     return CDGRAB_OK;
 }

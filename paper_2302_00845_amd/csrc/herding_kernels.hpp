@@ -10,6 +10,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "balance_kernels.hpp"
+
 namespace cdgrab {
 
 struct HerdingShape {
@@ -18,29 +20,48 @@ struct HerdingShape {
     int64_t seg_len;   // steps per segment (last one may be shorter)
 };
 
-__device__ __forceinline__ double herding_step_sum(const float *__restrict__ z, const int32_t *__restrict__ perm,
-                                                   const HerdingShape &sh, int64_t j, int64_t e) {
-    double v = 0.0;
+// Sum over the workers of elements e .. e+3 of step j's vectors.  VW = widest
+// aligned load every row start allows (as in the balancing kernels).
+template <int VW>
+__device__ __forceinline__ void herding_step_sum(const float *__restrict__ z, const int32_t *__restrict__ perm,
+                                                 const HerdingShape &sh, int64_t j, int64_t e, double v[4]) {
+    v[0] = v[1] = v[2] = v[3] = 0.0;
+#pragma unroll 8
     for (int64_t i = 0; i < sh.m; ++i) {
-        int64_t id = perm ? (int64_t)perm[i * sh.n + j] : j;
-        v += (double)z[(i * sh.n + id) * sh.d + e];
+        const int64_t id = perm ? (int64_t)perm[i * sh.n + j] : j;
+        const float4 x = load4<VW>(z + (i * sh.n + id) * sh.d, e, sh.d);
+        v[0] += (double)x.x;
+        v[1] += (double)x.y;
+        v[2] += (double)x.z;
+        v[3] += (double)x.w;
     }
-    return v;
 }
 
-// Pass A: segsum[s][e] = sum over the segment's steps and all workers.
+__device__ __forceinline__ int64_t herding_quads(const HerdingShape &sh) { return (sh.d + 3) / 4; }
+
+// Pass A: segsum[s][e] = sum over the segment's steps and all workers.  One thread
+// per (segment, four consecutive elements).
+template <int VW>
 __global__ __launch_bounds__(256) void herding_segment_sums(const float *__restrict__ z,
                                                             const int32_t *__restrict__ perm, HerdingShape sh,
                                                             double *__restrict__ segsum)
 {
+    const int64_t quads = herding_quads(sh);
     const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (g >= sh.segments * sh.d) return;
-    const int64_t s = g / sh.d, e = g - s * sh.d;
+    if (g >= sh.segments * quads) return;
+    const int64_t s = g / quads, e = (g - s * quads) * 4;
     const int64_t j0 = s * sh.seg_len;
     const int64_t j1 = (j0 + sh.seg_len < sh.n) ? j0 + sh.seg_len : sh.n;
-    double acc = 0.0;
-    for (int64_t j = j0; j < j1; ++j) acc += herding_step_sum(z, perm, sh, j, e);
-    segsum[g] = acc;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int64_t j = j0; j < j1; ++j) {
+        double v[4];
+        herding_step_sum<VW>(z, perm, sh, j, e, v);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] += v[q];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (e + q < sh.d) segsum[s * sh.d + e + q] = acc[q];
 }
 
 // Pass B (one thread per element): zbar[e] and start[s][e], the centred prefix
@@ -67,6 +88,7 @@ __global__ __launch_bounds__(256) void herding_segment_offsets(const double *__r
 // Pass C: replay each segment from its starting prefix; the largest |prefix| seen
 // anywhere is folded into *bound with an integer max on the bit pattern (valid
 // for non-negative doubles).
+template <int VW>
 __global__ __launch_bounds__(256) void herding_prefix_max(const float *__restrict__ z,
                                                           const int32_t *__restrict__ perm, HerdingShape sh,
                                                           const double *__restrict__ zbar,
@@ -74,17 +96,28 @@ __global__ __launch_bounds__(256) void herding_prefix_max(const float *__restric
                                                           unsigned long long *__restrict__ bound_bits)
 {
     __shared__ double wave_max[4];
+    const int64_t quads = herding_quads(sh);
     const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
     double mx = 0.0;
-    if (g < sh.segments * sh.d) {
-        const int64_t s = g / sh.d, e = g - s * sh.d;
+    if (g < sh.segments * quads) {
+        const int64_t s = g / quads, e = (g - s * quads) * 4;
         const int64_t j0 = s * sh.seg_len;
         const int64_t j1 = (j0 + sh.seg_len < sh.n) ? j0 + sh.seg_len : sh.n;
-        const double centre = (double)sh.m * zbar[e];
-        double acc = start[g];
+        double centre[4], acc[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const bool in = e + q < sh.d;  // elements beyond d load as zero and stay zero
+            centre[q] = in ? (double)sh.m * zbar[e + q] : 0.0;
+            acc[q] = in ? start[s * sh.d + e + q] : 0.0;
+        }
         for (int64_t j = j0; j < j1; ++j) {
-            acc += herding_step_sum(z, perm, sh, j, e) - centre;
-            mx = fmax(mx, fabs(acc));
+            double v[4];
+            herding_step_sum<VW>(z, perm, sh, j, e, v);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                acc[q] += v[q] - centre[q];
+                mx = fmax(mx, fabs(acc[q]));
+            }
         }
     }
 #pragma unroll

@@ -97,10 +97,14 @@ __global__ void column_mean(const float *__restrict__ rows, int64_t n, int64_t d
 
 // ---------------------------------------------------------------------------
 // Per-example gradient of softmax cross-entropy for a linear model ("CD-GraB
-// Workers", line 4).  One wavefront per example: the example's features are
-// staged in LDS, the logits are wave-reduced one class at a time, and the
-// (in_dim+1) x classes outer product is written with coalesced stores -- the
-// kernel is bound by that write (about ten times the bytes it reads).
+// Workers", line 4).  One wavefront per example, each wavefront looping over
+// examples: the example's features are staged in LDS, the logits are
+// wave-reduced one class at a time, and the (in_dim+1) x classes outer product
+// is written with coalesced 16-byte stores -- the kernel is bound by that write
+// (about ten times the bytes it reads).  WLDS: the workgroup first copies the
+// weights into LDS (rows padded to the odd length `wstride`, so that lanes on
+// consecutive rows hit distinct banks); without it the weights are read from
+// global memory with row length wstride = classes.
 constexpr int kGradWaves = 4;
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -109,60 +113,102 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Orders one wavefront's LDS writes before its later LDS reads from other lanes.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <bool WLDS>
 __global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *__restrict__ X,
                                                                    const int32_t *__restrict__ y,
                                                                    const float *__restrict__ W,
                                                                    float *__restrict__ G, int64_t N,
-                                                                   int in_dim, int classes)
+                                                                   int in_dim, int classes, int wstride)
 {
-    extern __shared__ float dyn[];  // per wave: in_dim + 1 features, then `classes` deltas
+    // [WLDS: (in_dim + 1) x wstride weights] then per wave: in_dim + 1 features, `classes` deltas
+    extern __shared__ float dyn[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int per_wave = in_dim + 1 + classes;
+    const int dd = (in_dim + 1) * classes;
+    const float *Wv = W;
     float *xs = dyn + wave * per_wave;
+    if (WLDS) {
+        float *Wl = dyn;
+        xs += (in_dim + 1) * wstride;
+        const int qs = (kGradWaves * 64) / classes, rs = (kGradWaves * 64) % classes;
+        int r = (int)threadIdx.x / classes;
+        int c = (int)threadIdx.x - r * classes;
+        for (int f = threadIdx.x; f < dd; f += kGradWaves * 64) {
+            Wl[r * wstride + c] = W[f];
+            r += qs;
+            c += rs;
+            if (c >= classes) { c -= classes; ++r; }
+        }
+        __syncthreads();
+        Wv = Wl;
+    }
     float *delta = xs + in_dim + 1;
-    const int64_t e = (int64_t)blockIdx.x * kGradWaves + wave;
-    const bool active = e < N;  // inactive waves still reach every barrier
 
-    if (active) {
+    for (int64_t e = (int64_t)blockIdx.x * kGradWaves + wave; e < N; e += (int64_t)gridDim.x * kGradWaves) {
         const float *x = X + e * in_dim;
+#pragma unroll 8
         for (int r = lane; r < in_dim; r += 64) xs[r] = x[r];
         if (lane == 0) xs[in_dim] = 1.0f;  // bias input
-    }
-    __syncthreads();
+        wave_lds_sync();
 
-    float mx = -INFINITY;
-    if (active) {
+        float mx = -INFINITY;
         for (int c = 0; c < classes; ++c) {
             float part = 0.f;
-            for (int r = lane; r <= in_dim; r += 64) part = fmaf(xs[r], W[(int64_t)r * classes + c], part);
-            float z = wave_sum(part);
+#pragma unroll 4
+            for (int r = lane; r <= in_dim; r += 64) part = fmaf(xs[r], Wv[r * wstride + c], part);
+            const float z = wave_sum(part);
             if (lane == 0) delta[c] = z;
             mx = fmaxf(mx, z);
         }
-    }
-    __syncthreads();
-    float Z = 0.f;
-    if (active) {
+        wave_lds_sync();
+        float Z = 0.f;
         for (int c = lane; c < classes; c += 64) Z += expf(delta[c] - mx);
         Z = wave_sum(Z);
-    }
-    __syncthreads();
-    if (active) {
         const int label = y[e];
-        for (int c = lane; c < classes; c += 64) {
-            float p = expf(delta[c] - mx) / Z;
+        for (int c = lane; c < classes; c += 64) {  // each lane rewrites only what it read
+            const float p = expf(delta[c] - mx) / Z;
             delta[c] = p - (c == label ? 1.0f : 0.0f);
         }
-    }
-    __syncthreads();
-    if (active) {
-        const int64_t dd = (int64_t)(in_dim + 1) * classes;
-        float *g = G + e * dd;
-        for (int64_t idx = lane; idx < dd; idx += 64) {
-            int r = (int)(idx / classes);
-            int c = (int)(idx - (int64_t)r * classes);
-            g[idx] = xs[r] * delta[c];
+        wave_lds_sync();
+
+        // row e of G, element idx = r * classes + c.  A scalar head brings the row to a
+        // 16-byte boundary, the body goes out as four-element stores, a scalar tail ends
+        // it; (r, c) advances by increments, with no division inside the loop.
+        float *g = G + e * (int64_t)dd;
+        int head = (int)(((16u - (uint32_t)(reinterpret_cast<uintptr_t>(g) & 15u)) & 15u) >> 2);
+        if (head > dd) head = dd;
+        const int nvec = (dd - head) >> 2;
+        const int tail0 = head + 4 * nvec;
+        if (lane < head) g[lane] = xs[lane / classes] * delta[lane % classes];
+        if (lane < dd - tail0) {
+            const int idx = tail0 + lane;
+            g[idx] = xs[idx / classes] * delta[idx % classes];
         }
+        const int qs = 256 / classes, rs = 256 % classes;
+        int r = (head + 4 * lane) / classes;
+        int c = (head + 4 * lane) - r * classes;
+#pragma unroll 2
+        for (int v = lane; v < nvec; v += 64) {
+            int rr = r, cc = c;
+            float o[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                o[q] = xs[rr] * delta[cc];
+                if (++cc == classes) { cc = 0; ++rr; }
+            }
+            *reinterpret_cast<float4 *>(g + head + 4 * v) = make_float4(o[0], o[1], o[2], o[3]);
+            r += qs;
+            c += rs;
+            if (c >= classes) { c -= classes; ++r; }
+        }
+        wave_lds_sync();  // the next example overwrites xs and delta
     }
 }
 

@@ -48,7 +48,8 @@ def test_reorder_rejects_bad_sign(lib):
     assert ei.value.code == -1
 
 
-@pytest.mark.parametrize("N,in_dim,classes", [(1, 1, 1), (5, 7, 4), (64, 784, 10), (257, 784, 10), (33, 100, 70)])
+@pytest.mark.parametrize("N,in_dim,classes", [(1, 1, 1), (5, 7, 4), (64, 784, 10), (257, 784, 10), (33, 100, 70),
+                                               (9, 2000, 12), (300, 33, 300), (9000, 30, 3)])
 def test_pergrad_matches_oracle(lib, N, in_dim, classes):
     X, y, W = workloads.softmax_problem(N, N, in_dim, classes)
     if classes > 1:
