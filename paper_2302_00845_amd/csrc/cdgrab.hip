@@ -581,16 +581,22 @@ int train_generate(void *vctx, int64_t first_pair, int64_t count, float *staging
     cdgrab_handle *h = c->h;
     if (first_pair % c->m != 0 || count % c->m != 0) return 1;  // chunks are whole step pairs
     const int64_t k_first = first_pair / c->m, k_count = count / c->m;
-    const size_t lds = (size_t)kGradWaves * (size_t)(c->in_dim + 1 + c->classes) * sizeof(float);
+    const size_t lds = (size_t)c->classes * sizeof(float);
     for (int64_t j = 2 * k_first; j < 2 * (k_first + k_count); ++j) {
-        hipLaunchKernelGGL(train_step_delta, dim3((unsigned)((c->m + kGradWaves - 1) / kGradWaves)),
-                           dim3(kGradWaves * 64), lds, static_cast<hipStream_t>(stream), c->X, c->y,
+        hipLaunchKernelGGL(train_step_delta, dim3((unsigned)c->m), dim3(kDeltaWaves * 64), lds,
+                           static_cast<hipStream_t>(stream), c->X, c->y,
                            c->perm_in, c->W, h->train_delta, c->loss_out, c->m, c->n, j, (int)c->in_dim,
                            (int)c->classes);
-        hipLaunchKernelGGL(train_step_update, dim3((unsigned)((c->d + 255) / 256)), dim3(256), 0,
-                           static_cast<hipStream_t>(stream), c->X, c->perm_in, h->train_delta, c->W,
-                           c->velocity, staging, c->grads_out, c->m, c->n, j, k_first, (int)c->in_dim,
-                           (int)c->classes, c->lr, c->momentum);
+        if (c->perm_in)
+            hipLaunchKernelGGL(train_step_update<true>, dim3((unsigned)((c->d + 255) / 256)), dim3(256), 0,
+                               static_cast<hipStream_t>(stream), c->X, c->perm_in, h->train_delta, c->W,
+                               c->velocity, staging, c->grads_out, c->m, c->n, j, k_first, (int)c->in_dim,
+                               (int)c->classes, c->lr, c->momentum);
+        else
+            hipLaunchKernelGGL(train_step_update<false>, dim3((unsigned)((c->d + 255) / 256)), dim3(256), 0,
+                               static_cast<hipStream_t>(stream), c->X, c->perm_in, h->train_delta, c->W,
+                               c->velocity, staging, c->grads_out, c->m, c->n, j, k_first, (int)c->in_dim,
+                               (int)c->classes, c->lr, c->momentum);
     }
     return hipGetLastError() == hipSuccess ? 0 : 2;
 }
@@ -607,8 +613,6 @@ int cdgrab_train_epoch_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t i
         return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: null pointer");
     if (momentum != 0.0f && !velocity)
         return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: momentum needs a velocity buffer");
-    if ((size_t)kGradWaves * (size_t)(in_dim + 1 + classes) * sizeof(float) > 64 * 1024)
-        return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: in_dim + classes too large for LDS staging");
     HIP_TRY(h, hipSetDevice(h->device));
     int rc = ensure(h, h->train_delta, h->train_delta_cap, m * classes);
     if (rc) return rc;

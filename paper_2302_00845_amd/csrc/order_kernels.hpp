@@ -217,53 +217,52 @@ __global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *
 // with the server's average, "CD-GraB Parameter Server" lines 5-7), for the
 // softmax-regression model.  Step j: worker i takes example perm[i][j].
 //
-// train_step_delta: one wavefront per worker computes delta_i = softmax(W^T [x;1]) - onehot(y)
-// at the current weights, and the example's loss.
-__global__ __launch_bounds__(kGradWaves * 64) void train_step_delta(const float *__restrict__ X,
-                                                                    const int32_t *__restrict__ y,
-                                                                    const int32_t *__restrict__ perm,
-                                                                    const float *__restrict__ W,
-                                                                    float *__restrict__ delta_out,
-                                                                    float *__restrict__ loss_out, int64_t m,
-                                                                    int64_t n, int64_t j, int in_dim,
-                                                                    int classes)
+// train_step_delta: one workgroup per worker computes delta_i = softmax(W^T [x;1]) - onehot(y)
+// at the current weights, and the example's loss.  Each of the sixteen wavefronts
+// takes classes w, w + 16, ..: its lanes split the rows of the dot product, with
+// all loads of one class in flight together (the step is a chain of dependent
+// launches, so latency is what counts), and a wave reduction gives the logit.
+// One wavefront then takes the softmax.
+constexpr int kDeltaWaves = 16;
+
+__global__ __launch_bounds__(kDeltaWaves * 64) void train_step_delta(const float *__restrict__ X,
+                                                                     const int32_t *__restrict__ y,
+                                                                     const int32_t *__restrict__ perm,
+                                                                     const float *__restrict__ W,
+                                                                     float *__restrict__ delta_out,
+                                                                     float *__restrict__ loss_out, int64_t m,
+                                                                     int64_t n, int64_t j, int in_dim,
+                                                                     int classes)
 {
-    extern __shared__ float dyn[];
+    extern __shared__ float logit[];  // `classes` floats
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int per_wave = in_dim + 1 + classes;
-    float *xs = dyn + wave * per_wave;
-    float *logit = xs + in_dim + 1;
-    const int64_t i = (int64_t)blockIdx.x * kGradWaves + wave;
-    const bool active = i < m;
-    int64_t id = 0;
-    if (active) {
-        id = perm ? (int64_t)perm[i * n + j] : j;
-        const float *x = X + (i * n + id) * in_dim;
-        for (int r = lane; r < in_dim; r += 64) xs[r] = x[r];
-        if (lane == 0) xs[in_dim] = 1.0f;
+    const int64_t i = blockIdx.x;  // worker
+    const int64_t id = perm ? (int64_t)perm[i * n + j] : j;
+    const float *x = X + (i * n + id) * in_dim;
+    for (int c = wave; c < classes; c += kDeltaWaves) {
+        float part = 0.f;
+#pragma unroll 16
+        for (int r = lane; r <= in_dim; r += 64) {
+            const float xv = x[r < in_dim ? r : in_dim - 1];
+            part = fmaf(r < in_dim ? xv : 1.0f, W[r * classes + c], part);  // bias input 1
+        }
+        const float z = wave_sum(part);
+        if (lane == 0) logit[c] = z;
     }
     __syncthreads();
+    if (wave != 0) return;
     float mx = -INFINITY;
-    if (active) {
-        for (int c = 0; c < classes; ++c) {
-            float part = 0.f;
-            for (int r = lane; r <= in_dim; r += 64) part = fmaf(xs[r], W[(int64_t)r * classes + c], part);
-            float z = wave_sum(part);
-            if (lane == 0) logit[c] = z;
-            mx = fmaxf(mx, z);
-        }
-    }
-    __syncthreads();
-    if (active) {
-        float Z = 0.f;
-        for (int c = lane; c < classes; c += 64) Z += expf(logit[c] - mx);
-        Z = wave_sum(Z);
-        const int label = y[i * n + id];
-        for (int c = lane; c < classes; c += 64) {
-            float p = expf(logit[c] - mx) / Z;
-            delta_out[i * classes + c] = p - (c == label ? 1.0f : 0.0f);
-            if (c == label && loss_out) loss_out[i * n + j] = -(logit[c] - mx - logf(Z));
-        }
+    for (int c = lane; c < classes; c += 64) mx = fmaxf(mx, logit[c]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    float Z = 0.f;
+    for (int c = lane; c < classes; c += 64) Z += expf(logit[c] - mx);
+    Z = wave_sum(Z);
+    const int label = y[i * n + id];
+    for (int c = lane; c < classes; c += 64) {
+        const float p = expf(logit[c] - mx) / Z;
+        delta_out[i * classes + c] = p - (c == label ? 1.0f : 0.0f);
+        if (c == label && loss_out) loss_out[i * n + j] = -(logit[c] - mx - logf(Z));
     }
 }
 
@@ -272,6 +271,7 @@ __global__ __launch_bounds__(kGradWaves * 64) void train_step_delta(const float 
 // chunk holds rows [2q], [2q+1] with q = (k - k_first) m + i) and optionally into
 // grads_out[m][n][d], forms the average gradient and applies SGD with momentum
 // (v <- momentum v + gbar; w <- w - lr v).
+template <bool PERM>
 __global__ __launch_bounds__(256) void train_step_update(const float *__restrict__ X,
                                                          const int32_t *__restrict__ perm,
                                                          const float *__restrict__ delta,
@@ -286,17 +286,30 @@ __global__ __launch_bounds__(256) void train_step_update(const float *__restrict
     if (p >= d) return;
     const int r = (int)(p / classes);
     const int c = (int)(p - (int64_t)r * classes);
+    const int rx = r < in_dim ? r : in_dim - 1;  // the bias row reads a valid feature and drops it
     const int64_t k = j >> 1;
     const int which = (int)(j & 1);
+    constexpr int U = 8;  // workers per batch: all of a batch's loads are issued before its stores
     float sum = 0.f;
-    for (int64_t i = 0; i < m; ++i) {
-        const int64_t id = perm ? (int64_t)perm[i * n + j] : j;
-        const float xr = (r < in_dim) ? X[(i * n + id) * in_dim + r] : 1.0f;
-        const float g = xr * delta[i * classes + c];
-        const int64_t q = (k - k_first) * m + i;
-        staging[(2 * q + which) * d + p] = g;
-        if (grads_out) grads_out[(i * n + j) * d + p] = g;
-        sum += g;
+    for (int64_t i0 = 0; i0 < m; i0 += U) {
+        float g[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = (i0 + u < m) ? i0 + u : m - 1;
+            const int64_t id = PERM ? (int64_t)perm[i * n + j] : j;
+            const float xv = X[(i * n + id) * in_dim + rx];
+            g[u] = (r < in_dim ? xv : 1.0f) * delta[i * classes + c];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = i0 + u;
+            if (i < m) {
+                const int64_t q = (k - k_first) * m + i;
+                staging[(2 * q + which) * d + p] = g[u];
+                if (grads_out) grads_out[(i * n + j) * d + p] = g[u];
+                sum += g[u];
+            }
+        }
     }
     const float gbar = sum / (float)m;
     float step = gbar;
