@@ -98,6 +98,36 @@ def test_multi_epoch_training_lowers_loss(lib):
     assert losses[-1] < 0.6 * losses[0]
 
 
+def test_cdgrab_order_beats_random_reshuffling(lib):
+    """The convergence claim of Sec. 4 / Sec. 5, observed on a synthetic softmax regression with
+    labels drawn from the model (so the optimum has non-zero per-example gradients): at a
+    constant step size, carrying CD-GraB's permutations over the epochs drives the norm of
+    the full gradient several times lower than drawing fresh random permutations every
+    epoch (distributed random reshuffling).  Measured: 5.2e-3 against 2.6e-2 after 20 epochs."""
+    m, n, in_dim, classes, lr, T = 16, 256, 32, 10, 0.2, 20
+    final = {"cd": [], "rr": []}
+    for seed in range(2):
+        rng = np.random.default_rng(seed)
+        Wtrue = rng.standard_normal((in_dim + 1, classes))
+        X = rng.standard_normal((m, n, in_dim)).astype(np.float32)
+        logits = np.concatenate([X, np.ones((m, n, 1), np.float32)], -1) @ Wtrue
+        y = (logits + rng.gumbel(size=logits.shape)).argmax(-1).astype(np.int32)
+        Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+        for mode in ("cd", "rr"):
+            h = lib.Handle()
+            W = torch.zeros((in_dim + 1, classes), dtype=torch.float32, device="cuda")
+            perm = torch.from_numpy(workloads.random_perms(seed, m, n)).cuda()
+            for epoch in range(T):
+                out = lib.cdgrab_train_epoch_softmax(h, Xd, yd, W, perm_in=perm, lr=lr)
+                perm = out["perm"] if mode == "cd" else \
+                    torch.from_numpy(workloads.random_perms(1000 * seed + epoch + 1, m, n)).cuda()
+            G = lib.cdgrab_pergrad(h, Xd.view(m * n, in_dim), yd.view(-1), W)
+            final[mode].append(float(G.double().mean(0).norm()))
+    print("full-gradient norm after %d epochs:" % T, final)
+    assert np.mean(final["cd"]) < 0.5 * np.mean(final["rr"])
+    assert all(c < r for c, r in zip(final["cd"], final["rr"]))
+
+
 def test_argument_errors(lib):
     h = lib.Handle()
     X = torch.zeros((2, 3, 4), dtype=torch.float32, device="cuda")
