@@ -350,12 +350,15 @@ int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
     if (per_cu < 1) per_cu = 1;
     int64_t groups = (N + kGradWaves - 1) / kGradWaves;
     if (groups > per_cu * h->num_cu) groups = per_cu * h->num_cu;
-    if (wlds)
-        hipLaunchKernelGGL(softmax_pergrad<true>, dim3((unsigned)groups), dim3(kGradWaves * 64), lds, h->stream,
-                           X, y, W, G_out, N, (int)in_dim, (int)classes, wstride);
-    else
-        hipLaunchKernelGGL(softmax_pergrad<false>, dim3((unsigned)groups), dim3(kGradWaves * 64), lds,
-                           h->stream, X, y, W, G_out, N, (int)in_dim, (int)classes, (int)classes);
+    const bool prefetch = in_dim <= 64 * kGradPrefetch;
+    auto launch = [&](auto kernel, int stride) {
+        hipLaunchKernelGGL(kernel, dim3((unsigned)groups), dim3(kGradWaves * 64), lds, h->stream, X, y, W,
+                           G_out, N, (int)in_dim, (int)classes, stride);
+    };
+    if (wlds && prefetch) launch(softmax_pergrad<true, true>, wstride);
+    else if (wlds) launch(softmax_pergrad<true, false>, wstride);
+    else if (prefetch) launch(softmax_pergrad<false, true>, (int)classes);
+    else launch(softmax_pergrad<false, false>, (int)classes);
     HIP_TRY(h, hipGetLastError());
     return CDGRAB_OK;
 }

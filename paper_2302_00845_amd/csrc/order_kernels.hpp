@@ -105,7 +105,8 @@ __global__ void column_mean(const float *__restrict__ rows, int64_t n, int64_t d
 // weights into LDS (rows padded to the odd length `wstride`, so that lanes on
 // consecutive rows hit distinct banks); without it the weights are read from
 // global memory with row length wstride = classes.
-constexpr int kGradWaves = 4;
+constexpr int kGradWaves = 8;
+constexpr int kGradPrefetch = 16;  // feature registers per lane of the prefetch variant
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -120,7 +121,7 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <bool WLDS>
+template <bool WLDS, bool PREFETCH>
 __global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *__restrict__ X,
                                                                    const int32_t *__restrict__ y,
                                                                    const float *__restrict__ W,
@@ -151,10 +152,37 @@ __global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *
     }
     float *delta = xs + in_dim + 1;
 
-    for (int64_t e = (int64_t)blockIdx.x * kGradWaves + wave; e < N; e += (int64_t)gridDim.x * kGradWaves) {
-        const float *x = X + e * in_dim;
+    // PREFETCH (in_dim <= 64 * kGradPrefetch): the next example's features are loaded
+    // into registers while this example is worked on.
+    const int64_t e_step = (int64_t)gridDim.x * kGradWaves;
+    int64_t e = (int64_t)blockIdx.x * kGradWaves + wave;
+    float xn[kGradPrefetch];
+    if (PREFETCH && e < N) {
+#pragma unroll
+        for (int k = 0; k < kGradPrefetch; ++k) {
+            const int r = lane + 64 * k;
+            xn[k] = (r < in_dim) ? X[e * in_dim + r] : 0.f;
+        }
+    }
+    for (; e < N; e += e_step) {
+        if (PREFETCH) {
+#pragma unroll
+            for (int k = 0; k < kGradPrefetch; ++k) {
+                const int r = lane + 64 * k;
+                if (r < in_dim) xs[r] = xn[k];
+            }
+            if (e + e_step < N) {
+#pragma unroll
+                for (int k = 0; k < kGradPrefetch; ++k) {
+                    const int r = lane + 64 * k;
+                    xn[k] = (r < in_dim) ? X[(e + e_step) * in_dim + r] : 0.f;
+                }
+            }
+        } else {
+            const float *x = X + e * in_dim;
 #pragma unroll 8
-        for (int r = lane; r < in_dim; r += 64) xs[r] = x[r];
+            for (int r = lane; r < in_dim; r += 64) xs[r] = x[r];
+        }
         if (lane == 0) xs[in_dim] = 1.0f;  // bias input
         wave_lds_sync();
 
