@@ -96,37 +96,47 @@ SYN_FN float syn_inv_cbrt(float w) {
 
 /* Student-t(3) variate for (row, element); also returns the 16 mask bits. */
 SYN_FN float syn_student_t3(uint64_t seed_mixed, uint64_t row, uint64_t elem, uint32_t *mask_bits) {
-    float t = 0.0f;
+    /* rejection loop: only the draw and the disc test, so that lanes of a wavefront
+     * that accept at different draws do not repeat the transform below */
+    float u = 0.0f, w = 2.0f;
     *mask_bits = 0;
     for (uint32_t draw = 0; draw < 64; ++draw) {
         uint64_t x = syn_word(seed_mixed, row, elem, draw);
         if (draw == 0) *mask_bits = (uint32_t)(x & 0xffffu);
-        float u = syn_uniform_pm1((uint32_t)(x >> 40));
-        float v = syn_uniform_pm1((uint32_t)(x >> 16) & 0xffffffu);
-        float uu = u * u;
-        float vv = v * v;
-        float w = uu + vv;
-        if (w <= 1.0f) {
-            float y = syn_inv_cbrt(w);
-            float c = y * y;            /* w^(-2/3) */
-            float num = 3.0f * (c - 1.0f);
-            if (num < 0.0f) num = 0.0f; /* rounding when w is 1 */
-            float q = num / w;
-            t = u * __builtin_sqrtf(q);
+        float uc = syn_uniform_pm1((uint32_t)(x >> 40));
+        float vc = syn_uniform_pm1((uint32_t)(x >> 16) & 0xffffffu);
+        float uu = uc * uc;
+        float vv = vc * vc;
+        float wc = uu + vv;
+        if (wc <= 1.0f) {
+            u = uc;
+            w = wc;
             break;
         }
     }
-    return t;
+    if (w > 1.0f) return 0.0f;  /* 64 rejections in a row: probability 1e-43 */
+    float y = syn_inv_cbrt(w);
+    float c = y * y;            /* w^(-2/3) */
+    float num = 3.0f * (c - 1.0f);
+    if (num < 0.0f) num = 0.0f; /* rounding when w is 1 */
+    float q = num / w;
+    return u * __builtin_sqrtf(q);
 }
 
-SYN_FN float syn_element(const synth_params *p, uint64_t seed_mixed, int64_t row, int64_t e) {
+/* Element e of a row; `block` = e / block_len (ignored without block scales). */
+SYN_FN float syn_element_in_block(const synth_params *p, uint64_t seed_mixed, int64_t row, int64_t e,
+                                  int64_t block) {
     uint32_t mask_bits;
     float t = syn_student_t3(seed_mixed, (uint64_t)row, (uint64_t)e, &mask_bits);
     if (mask_bits < p->zero_threshold) return 0.0f;
     float noise = p->row_scale[row] * t;
     float v = p->mu[e] + noise;
-    if (p->n_block_scales > 0) v = v * p->block_scale[e / p->block_len];
+    if (p->n_block_scales > 0) v = v * p->block_scale[block];
     return v;
+}
+
+SYN_FN float syn_element(const synth_params *p, uint64_t seed_mixed, int64_t row, int64_t e) {
+    return syn_element_in_block(p, seed_mixed, row, e, p->n_block_scales > 0 ? e / p->block_len : 0);
 }
 
 SYN_FN uint64_t syn_seed_mixed(uint64_t seed) { return syn_mix(seed ^ 0x5bd1e9955bd1e995ULL) | 1ULL; }

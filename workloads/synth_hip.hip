@@ -16,8 +16,20 @@ __global__ __launch_bounds__(256) void synth_fill_kernel(synth_params p, uint64_
     const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
     for (int64_t e = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; e < p.d; e += stride) {
         float v[4];
+        // one division per four elements: the scale block of e, stepped when an element crosses into the next
+        int64_t block = 0, left = 0;
+        if (p.n_block_scales > 0) {
+            block = (p.d <= 0xffffffffll) ? (int64_t)((uint32_t)e / (uint32_t)p.block_len) : e / p.block_len;
+            left = (block + 1) * p.block_len - e;  // elements of this block from e on
+        }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = (e + q < p.d) ? syn_element(&p, seed_mixed, row, e + q) : 0.0f;
+        for (int q = 0; q < 4; ++q) {
+            // (blocks shorter than four elements can be crossed twice: divide again)
+            const int64_t b = (p.n_block_scales <= 0 || q < left) ? block
+                              : (p.block_len >= 4)                 ? block + 1
+                                                                   : (e + q) / p.block_len;
+            v[q] = (e + q < p.d) ? syn_element_in_block(&p, seed_mixed, row, e + q, b) : 0.0f;
+        }
         if (e + 3 < p.d && (p.d & 3) == 0) {
             *reinterpret_cast<float4 *>(out + e) = make_float4(v[0], v[1], v[2], v[3]);
         } else {
