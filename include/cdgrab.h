@@ -116,7 +116,8 @@ int cdgrab_plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs,
  *   G_out [N][(in_dim+1)*classes] fp32 dev:
  *     delta = softmax(W^T [x;1]) - onehot(y);
  *     G_out[e][r*classes + c] = x_r * delta_c,  G_out[e][in_dim*classes + c] = delta_c.
- * fp32 arithmetic.  Errors: EINVAL (N<0, in_dim<1, classes<1 or >1024, null). */
+ * fp32 arithmetic.  Errors: EINVAL (N<0, in_dim<1, classes<1 or >1024, null,
+ * in_dim + 1 + classes > 16384: one example's staging must fit 64 KB of LDS). */
 int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
                    const float *X, const int32_t *y, const float *W, float *G_out);
 

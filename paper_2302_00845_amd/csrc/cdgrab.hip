@@ -335,9 +335,13 @@ int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
                     (long long)N, (long long)in_dim, (long long)classes);
     if (N == 0) return CDGRAB_OK;
     if (!X || !y || !W || !G_out) return fail(h, CDGRAB_EINVAL, "cdgrab_pergrad: null pointer");
-    const size_t lds_waves = (size_t)kGradWaves * (size_t)(in_dim + 1 + classes) * sizeof(float);
-    if (lds_waves > 64 * 1024)
+    // per-wave staging of one example; fewer wavefronts per workgroup when it is long
+    const size_t per_wave = (size_t)(in_dim + 1 + classes) * sizeof(float);
+    if (per_wave > 64 * 1024)
         return fail(h, CDGRAB_EINVAL, "cdgrab_pergrad: in_dim + classes too large for LDS staging");
+    int waves = kGradWaves;
+    while (waves > 1 && waves * per_wave > 64 * 1024) waves >>= 1;
+    const size_t lds_waves = waves * per_wave;
     HIP_TRY(h, hipSetDevice(h->device));
     // weights in LDS when they fit beside the per-wave staging (64 KB per workgroup)
     const int wstride = (int)classes | 1;
@@ -346,13 +350,11 @@ int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
     const size_t lds = lds_waves + (wlds ? lds_w : 0);
     // each wavefront loops over examples: as many workgroups as stay resident
     int64_t per_cu = (int64_t)((160 * 1024) / lds);
-    if (per_cu > 8) per_cu = 8;
-    if (per_cu < 1) per_cu = 1;
-    int64_t groups = (N + kGradWaves - 1) / kGradWaves;
-    if (groups > per_cu * h->num_cu) groups = per_cu * h->num_cu;
+    per_cu = std::max<int64_t>(1, std::min<int64_t>(per_cu, 32 / waves));
+    int64_t groups = std::min<int64_t>((N + waves - 1) / waves, per_cu * h->num_cu);
     const bool prefetch = in_dim <= 64 * kGradPrefetch;
     auto launch = [&](auto kernel, int stride) {
-        hipLaunchKernelGGL(kernel, dim3((unsigned)groups), dim3(kGradWaves * 64), lds, h->stream, X, y, W,
+        hipLaunchKernelGGL(kernel, dim3((unsigned)groups), dim3(waves * 64), lds, h->stream, X, y, W,
                            G_out, N, (int)in_dim, (int)classes, stride);
     };
     if (wlds && prefetch) launch(softmax_pergrad<true, true>, wstride);

@@ -105,7 +105,7 @@ __global__ void column_mean(const float *__restrict__ rows, int64_t n, int64_t d
 // weights into LDS (rows padded to the odd length `wstride`, so that lanes on
 // consecutive rows hit distinct banks); without it the weights are read from
 // global memory with row length wstride = classes.
-constexpr int kGradWaves = 8;
+constexpr int kGradWaves = 8;  // wavefronts per workgroup (fewer when the features are long)
 constexpr int kGradPrefetch = 16;  // feature registers per lane of the prefetch variant
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -131,6 +131,7 @@ __global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *
     // [WLDS: (in_dim + 1) x wstride weights] then per wave: in_dim + 1 features, `classes` deltas
     extern __shared__ float dyn[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nthreads = blockDim.x, nwaves = blockDim.x >> 6;  // 1 .. kGradWaves wavefronts
     const int per_wave = in_dim + 1 + classes;
     const int dd = (in_dim + 1) * classes;
     const float *Wv = W;
@@ -138,10 +139,10 @@ __global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *
     if (WLDS) {
         float *Wl = dyn;
         xs += (in_dim + 1) * wstride;
-        const int qs = (kGradWaves * 64) / classes, rs = (kGradWaves * 64) % classes;
+        const int qs = nthreads / classes, rs = nthreads % classes;
         int r = (int)threadIdx.x / classes;
         int c = (int)threadIdx.x - r * classes;
-        for (int f = threadIdx.x; f < dd; f += kGradWaves * 64) {
+        for (int f = threadIdx.x; f < dd; f += nthreads) {
             Wl[r * wstride + c] = W[f];
             r += qs;
             c += rs;
@@ -154,8 +155,8 @@ __global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *
 
     // PREFETCH (in_dim <= 64 * kGradPrefetch): the next example's features are loaded
     // into registers while this example is worked on.
-    const int64_t e_step = (int64_t)gridDim.x * kGradWaves;
-    int64_t e = (int64_t)blockIdx.x * kGradWaves + wave;
+    const int64_t e_step = (int64_t)gridDim.x * nwaves;
+    int64_t e = (int64_t)blockIdx.x * nwaves + wave;
     float xn[kGradPrefetch];
     if (PREFETCH && e < N) {
 #pragma unroll

@@ -49,11 +49,11 @@ def test_reorder_rejects_bad_sign(lib):
 
 
 @pytest.mark.parametrize("N,in_dim,classes", [(1, 1, 1), (5, 7, 4), (64, 784, 10), (257, 784, 10), (33, 100, 70),
-                                               (9, 2000, 12), (300, 33, 300), (9000, 30, 3)])
+                                               (9, 2000, 12), (300, 33, 300), (9000, 30, 3), (5, 6000, 7), (3, 16000, 3)])
 def test_pergrad_matches_oracle(lib, N, in_dim, classes):
     X, y, W = workloads.softmax_problem(N, N, in_dim, classes)
-    if classes > 1:
-        W = (W * 20).astype(np.float32)
+    if classes > 1 and in_dim <= 2000:
+        W = (W * 20).astype(np.float32)       # logits of order one; with long features they already are
     h = lib.Handle()
     G = lib.cdgrab_pergrad(h, torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(),
                            torch.from_numpy(W).cuda()).cpu().numpy()
@@ -74,6 +74,11 @@ def test_pergrad_empty_and_errors(lib):
     assert lib.cdgrab_pergrad(h, X, y, W).shape == (0, 18)
     with pytest.raises(TypeError):
         lib.cdgrab_pergrad(h, X.double(), y, W)
+    big = torch.zeros((2, 20000), dtype=torch.float32, device="cuda")         # one example exceeds LDS
+    with pytest.raises(lib.CdgrabError) as ei:
+        lib.cdgrab_pergrad(h, big, torch.zeros(2, dtype=torch.int32, device="cuda"),
+                           torch.zeros((20001, 3), dtype=torch.float32, device="cuda"))
+    assert ei.value.code == -1
 
 
 def test_config2_softmax_end_to_end(lib):
