@@ -216,6 +216,22 @@ int cdgrab_train_epoch_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t i
                                float momentum, int8_t *signs_out, int32_t *perm_out,
                                float *grads_out, float *loss_out);
 
+/* T training epochs with the permutations carried over (the outer loop of "CD-GraB
+ * Workers" / "CD-GraB Parameter Server", Sec. 3.3: the order built while epoch t is
+ * balanced is the order epoch t+1 visits).  Equivalent to `epochs` calls of
+ * cdgrab_train_epoch_softmax, each taking the previous call's perm_out as perm_in.
+ *   perm [m][n] int32 dev, in/out: the first epoch's order on entry, the order the
+ *     next epoch would visit on return,
+ *   signs_out [m][n/2] int8 dev or NULL: the last epoch's pair signs,
+ *   loss_out [epochs][m][n] fp32 dev or NULL: loss of each example when it was visited.
+ * Other arguments as in cdgrab_train_epoch_softmax.  The handle keeps one spare
+ * permutation and one sign buffer.
+ * Errors: EINVAL (as above, epochs < 1, perm NULL), ENOMEM, EHIP. */
+int cdgrab_train_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t in_dim, int64_t classes,
+                         const float *X, const int32_t *y, int32_t *perm, float *W,
+                         float *velocity, float lr, float momentum, int64_t epochs,
+                         int8_t *signs_out, float *loss_out);
+
 /* Reorder from arbitrary per-example signs ("Reordering Vectors based on Balanced
  * Signs", Sec. 2.1), one independent problem per worker:
  *   perm_out[i] = concat(L_pos, reverse(L_neg)), L_pos / L_neg the entries of

@@ -16,6 +16,7 @@ from .cdgrab import (  # noqa: F401
     cdgrab_plan_epoch,
     cdgrab_reorder,
     cdgrab_train_epoch_softmax,
+    cdgrab_train_softmax,
     library_path,
     load_library,
 )

@@ -96,6 +96,9 @@ def load_library():
     lib.cdgrab_train_epoch_softmax.argtypes = [P, i64, i64, i64, i64, P, P, P, P, P, ctypes.c_float,
                                                ctypes.c_float, P, P, P, P]
     lib.cdgrab_train_epoch_softmax.restype = ctypes.c_int
+    lib.cdgrab_train_softmax.argtypes = [P, i64, i64, i64, i64, P, P, P, P, P, ctypes.c_float,
+                                         ctypes.c_float, i64, P, P]
+    lib.cdgrab_train_softmax.restype = ctypes.c_int
     lib.cdgrab_herding_bound.argtypes = [P, i64, i64, i64, P, P, P]
     lib.cdgrab_herding_bound.restype = ctypes.c_int
     lib.cdgrab_measure_read_bandwidth.argtypes = [P, i64, ctypes.POINTER(ctypes.c_double)]
@@ -272,6 +275,28 @@ def cdgrab_train_epoch_softmax(h: Handle, X: torch.Tensor, y: torch.Tensor, W: t
         grads.data_ptr() if grads is not None else None,
         loss.data_ptr() if loss is not None else None))
     return {"signs": signs, "perm": perm, "grads": grads, "loss": loss}
+
+
+def cdgrab_train_softmax(h: Handle, X: torch.Tensor, y: torch.Tensor, W: torch.Tensor,
+                         perm: torch.Tensor, epochs: int,
+                         velocity: Optional[torch.Tensor] = None, lr: float = 0.1,
+                         momentum: float = 0.0, want_loss: bool = True) -> dict:
+    """`epochs` CD-GraB training epochs with the permutations carried over; W, velocity
+    and perm[m][n] (first order in, next order out) are updated in place."""
+    m, n, in_dim = X.shape
+    classes = W.shape[1]
+    d = (in_dim + 1) * classes
+    dev = h.device
+    signs = torch.empty((m, n // 2), dtype=torch.int8, device=dev)
+    loss = torch.empty((epochs, m, n), dtype=torch.float32, device=dev) if want_loss else None
+    h._check(h._lib.cdgrab_train_softmax(
+        h._h, m, n, in_dim, classes,
+        _ptr(X, torch.float32, (m, n, in_dim), "X", dev), _ptr(y, torch.int32, (m, n), "y", dev),
+        _ptr(perm, torch.int32, (m, n), "perm", dev),
+        _ptr(W, torch.float32, (in_dim + 1, classes), "W", dev),
+        _ptr(velocity, torch.float32, (d,), "velocity", dev), lr, momentum, epochs,
+        signs.data_ptr(), loss.data_ptr() if loss is not None else None))
+    return {"signs": signs, "perm": perm, "loss": loss}
 
 
 def cdgrab_balance_epoch_independent(h: Handle, grads: torch.Tensor,

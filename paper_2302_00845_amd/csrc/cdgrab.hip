@@ -50,6 +50,8 @@ struct cdgrab_handle {
     const float *uniforms = nullptr;                      // caller's draws while a randomized epoch runs
     float *zero_row = nullptr; int64_t zero_row_cap = 0;  // a zero vector standing in for a missing stale mean
     float *train_delta = nullptr; int64_t train_delta_cap = 0;  // [m][classes] softmax deltas of one step
+    int32_t *train_perm = nullptr; int64_t train_perm_cap = 0;  // spare [m][n] order of the multi-epoch driver
+    int8_t *train_signs = nullptr; int64_t train_signs_cap = 0; // its [m][n/2] signs when the caller wants none
     double *herd_ws = nullptr; int64_t herd_cap = 0;      // herding evaluator: segment sums, starts, mean
     float *staging = nullptr;  int64_t staging_cap = 0;   // floats: two staging chunks (the fused pass reads the previous block too)
 
@@ -312,6 +314,8 @@ int cdgrab_destroy(cdgrab_handle *h) {
     if (h->flag) (void)hipFree(h->flag);
     if (h->herd_ws) (void)hipFree(h->herd_ws);
     if (h->train_delta) (void)hipFree(h->train_delta);
+    if (h->train_perm) (void)hipFree(h->train_perm);
+    if (h->train_signs) (void)hipFree(h->train_signs);
     if (h->zero_row) (void)hipFree(h->zero_row);
     if (h->staging) (void)hipFree(h->staging);
     delete h;
@@ -627,6 +631,35 @@ int cdgrab_train_epoch_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t i
     const int64_t step_pairs = std::max<int64_t>(1, 64 / m);
     return balance_epoch_impl(h, m, n, ctx.d, nullptr, train_generate, &ctx, step_pairs * m, perm_in,
                               signs_out, perm_out, nullptr, nullptr, nullptr);
+}
+
+int cdgrab_train_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t in_dim, int64_t classes,
+                         const float *X, const int32_t *y, int32_t *perm, float *W, float *velocity,
+                         float lr, float momentum, int64_t epochs, int8_t *signs_out, float *loss_out) {
+    if (!h) return CDGRAB_EINVAL;
+    if (epochs < 1 || !perm) return fail(h, CDGRAB_EINVAL, "cdgrab_train_softmax: need epochs>=1 and perm");
+    if (m < 1 || n < 2 || (n & 1) || m > INT32_MAX || n > INT32_MAX)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_train_softmax: bad sizes");
+    HIP_TRY(h, hipSetDevice(h->device));
+    int rc = ensure(h, h->train_perm, h->train_perm_cap, m * n);
+    if (rc) return rc;
+    if (!signs_out) {
+        rc = ensure(h, h->train_signs, h->train_signs_cap, m * (n / 2));
+        if (rc) return rc;
+        signs_out = h->train_signs;
+    }
+    // the order ping-pongs between the caller's buffer and the spare one
+    int32_t *cur = perm, *nxt = h->train_perm;
+    for (int64_t t = 0; t < epochs; ++t) {
+        rc = cdgrab_train_epoch_softmax(h, m, n, in_dim, classes, X, y, cur, W, velocity, lr, momentum,
+                                        signs_out, nxt, nullptr, loss_out ? loss_out + t * m * n : nullptr);
+        if (rc) return rc;
+        std::swap(cur, nxt);
+    }
+    if (cur != perm)
+        HIP_TRY(h, hipMemcpyAsync(perm, cur, (size_t)(m * n) * sizeof(int32_t), hipMemcpyDeviceToDevice,
+                                  h->stream));
+    return CDGRAB_OK;
 }
 
 int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,

@@ -31,7 +31,7 @@ def test_header_declares_the_expected_calls():
     names = declared_symbols()
     for required in ("cdgrab_pergrad", "cdgrab_balance_epoch", "cdgrab_reorder", "cdgrab_create",
                      "cdgrab_destroy", "cdgrab_last_error", "cdgrab_plan_epoch", "cdgrab_get_timing",
-                     "cdgrab_herding_bound", "cdgrab_train_epoch_softmax",
+                     "cdgrab_herding_bound", "cdgrab_train_epoch_softmax", "cdgrab_train_softmax",
                      "cdgrab_balance_epoch_independent", "cdgrab_measure_read_bandwidth",
                      "cdgrab_balance_epoch_stale_mean", "cdgrab_balance_epoch_randomized"):
         assert required in names

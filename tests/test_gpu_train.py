@@ -128,6 +128,38 @@ def test_cdgrab_order_beats_random_reshuffling(lib):
     assert all(c < r for c, r in zip(final["cd"], final["rr"]))
 
 
+@pytest.mark.parametrize("epochs", [1, 3, 4])
+def test_multi_epoch_driver_equals_repeated_epochs(lib, epochs):
+    """cdgrab_train_softmax = repeated cdgrab_train_epoch_softmax with the order carried
+    over: same weights, velocity, order, signs and losses, bit for bit; and the whole run
+    follows the double oracle doing the same."""
+    m, n, in_dim, classes, lr, mom = 6, 20, 9, 4, 0.3, 0.9
+    X, y, W0 = problem(5, m, n, in_dim, classes)
+    perm0 = workloads.random_perms(9, m, n)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    h = lib.Handle()
+    Wa = torch.from_numpy(W0.copy()).cuda()
+    va = torch.zeros(Wa.numel(), dtype=torch.float32, device="cuda")
+    pa = torch.from_numpy(perm0.copy()).cuda()
+    out = lib.cdgrab_train_softmax(h, Xd, yd, Wa, pa, epochs, velocity=va, lr=lr, momentum=mom)
+    Wb = torch.from_numpy(W0.copy()).cuda()
+    vb = torch.zeros(Wb.numel(), dtype=torch.float32, device="cuda")
+    pb = torch.from_numpy(perm0.copy()).cuda()
+    Wr, vr, pr = W0.astype(np.float64), None, perm0
+    for t in range(epochs):
+        step = lib.cdgrab_train_epoch_softmax(h, Xd, yd, Wb, perm_in=pb, velocity=vb, lr=lr, momentum=mom)
+        assert torch.equal(step["loss"], out["loss"][t])
+        pb = step["perm"]
+        ref = oracle.train_epoch_softmax(X, y, pr, Wr, vr, lr, mom)
+        Wr, vr = ref["W"], ref["v"]
+        # the oracle follows the order the GPU built (judged separately by check_epoch in the test above)
+        pr = pb.cpu().numpy()
+    assert torch.equal(Wa, Wb) and torch.equal(va, vb)
+    assert torch.equal(out["perm"], pb) and out["perm"].data_ptr() == pa.data_ptr()
+    assert torch.equal(out["signs"], step["signs"])
+    assert rel_l2(Wa.cpu().numpy(), Wr) <= 1e-5
+
+
 def test_argument_errors(lib):
     h = lib.Handle()
     X = torch.zeros((2, 3, 4), dtype=torch.float32, device="cuda")
@@ -139,3 +171,6 @@ def test_argument_errors(lib):
     y = torch.zeros((2, 4), dtype=torch.int32, device="cuda")
     with pytest.raises(lib.CdgrabError):
         lib.cdgrab_train_epoch_softmax(h, X, y, W, momentum=0.9)        # momentum without velocity
+    perm = torch.from_numpy(workloads.random_perms(0, 2, 4)).cuda()
+    with pytest.raises(lib.CdgrabError):
+        lib.cdgrab_train_softmax(h, X, y, W, perm, 0)                    # no epochs
