@@ -85,6 +85,28 @@ def test_coordination_matters_with_many_workers(lib):
     assert coord < 0.5 * indep and indep < rand
 
 
+def test_herding_bound_over_worker_counts(lib):
+    """The shape of App. E's figure at reduced scale (60 000 vectors, 16 dimensions, the
+    paper's worker counts): coordinated balancing stays flat and lowest as m grows, while
+    independent per-worker balancing climbs towards random orders.  Measured: coordinated
+    2.5 / 2.2 / 2.1 / 2.4 / 2.1, independent 5.6 / 8.6 / 10.0 / 14.9 / 18.2, random about 80."""
+    h = lib.Handle()
+    N, d = 60000, 16
+    vec = workloads.herding_vectors(11, N, d)
+    coord, indep, rand = [], [], []
+    for m in (5, 10, 20, 50, 100):
+        z = torch.from_numpy(vec.reshape(m, N // m, d)).cuda()
+        coord.append(gpu_bound(lib, h, z, _run_orders(lib, h, z, 8, True)))
+        indep.append(gpu_bound(lib, h, z, _run_orders(lib, h, z, 8, False)))
+        rand.append(gpu_bound(lib, h, z, workloads.random_perms(m, m, N // m)))
+    print("coordinated", ["%.2f" % b for b in coord], "independent", ["%.2f" % b for b in indep],
+          "random", ["%.1f" % b for b in rand])
+    assert max(coord) < 1.5 * min(coord)                       # flat in m
+    assert all(c < 0.6 * i for c, i in zip(coord, indep))      # and lowest
+    assert indep[-1] > 2.0 * indep[0] and indep[2] > indep[0]  # independent balancing degrades with m
+    assert all(i < r for i, r in zip(indep, rand))
+
+
 def test_synthetic_herding_study_reduced(lib):
     """App. E's synthetic study, scaled down (2^16 unit vectors in 16 dimensions
     instead of 10^6): CD-GraB's orders reach a parallel herding bound far below that
