@@ -339,10 +339,12 @@ __global__ __launch_bounds__(kThreads) void reduce_partials(const double *__rest
 // t_k = <r, d_k> + sum_{j<k, decided} eps_j G[j][k]; step j broadcasts t_j,
 // fixes eps_j = +1 if t_j <= 0 else -1 (or, given uniform draws, the randomized
 // rule) and updates the later lanes.
-constexpr int kResolveThreads = 1024;
+// Threads of the resolver's load phase: 1024, but 512 for 64-pair blocks, whose walk
+// keeps 64 doubles of the Gram matrix per lane in registers.
+template <int BB> constexpr int kResolveThreads = BB > 32 ? 512 : 1024;
 
 template <int BB>
-__global__ __launch_bounds__(kResolveThreads) void resolve_signs(const double *__restrict__ sliced, int nb,
+__global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const double *__restrict__ sliced, int nb,
                                                                  int64_t k0, int32_t i0, int32_t m, int64_t half_n,
                                                                  int8_t *__restrict__ eps_blk,
                                                                  int8_t *__restrict__ signs_out,
@@ -353,7 +355,7 @@ __global__ __launch_bounds__(kResolveThreads) void resolve_signs(const double *_
     __shared__ double G[BB][BB + 1];
     __shared__ double P[BB];
     // two consecutive entries per thread and step (16 B loads); GRAM and PART are even
-    for (int idx = 2 * threadIdx.x; idx < L::PART; idx += 2 * kResolveThreads) {
+    for (int idx = 2 * threadIdx.x; idx < L::PART; idx += 2 * kResolveThreads<BB>) {
         double2 val = make_double2(0.0, 0.0);
 #pragma unroll
         for (int s = 0; s < kReduceSlices; ++s) {

@@ -220,7 +220,7 @@ void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
 }
 template <int BB>
 void launch_resolve(cdgrab_handle *h, const RowMap &rm, int8_t *signs_out, double *dots_out) {
-    hipLaunchKernelGGL((resolve_signs<BB>), dim3(1), dim3(kResolveThreads), 0, h->stream, h->reduced, rm.nb,
+    hipLaunchKernelGGL((resolve_signs<BB>), dim3(1), dim3(kResolveThreads<BB>), 0, h->stream, h->reduced, rm.nb,
                        rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out, h->uniforms);
 }
 
