@@ -321,8 +321,11 @@ __global__ __launch_bounds__(kThreads) void reduce_partials(const double *__rest
     const int g0 = s0 + (int)((int64_t)sub * (s1 - s0) / kReduceSubs);
     const int g1 = s0 + (int)((int64_t)(sub + 1) * (s1 - s0) / kReduceSubs);
     double sum = 0.0;
-    if (entry < part)
+    if (entry < part) {
+        // the loads are independent: keep eight in flight (the adds stay in order)
+#pragma unroll 8
         for (int g = g0; g < g1; ++g) sum += partials[(int64_t)g * part + entry];
+    }
     subsum[sub][ent] = sum;
     __syncthreads();
     if (sub == 0 && entry < part) {
