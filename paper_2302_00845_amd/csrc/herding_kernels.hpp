@@ -73,10 +73,12 @@ __global__ __launch_bounds__(256) void herding_segment_offsets(const double *__r
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= sh.d) return;
     double total = 0.0;
+#pragma unroll 8
     for (int64_t s = 0; s < sh.segments; ++s) total += segsum[s * sh.d + e];
     const double mean = total / (double)(sh.m * sh.n);
     zbar[e] = mean;
     double run = 0.0;
+#pragma unroll 8
     for (int64_t s = 0; s < sh.segments; ++s) {
         start[s * sh.d + e] = run;
         const int64_t j0 = s * sh.seg_len;
