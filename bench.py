@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--apply-mode", type=int, default=0,
                     help="0: library's choice by row length; 1: separate apply launch per block; "
                          "2: apply fused into the next block's dot/Gram launch")
+    ap.add_argument("--gram-mode", type=int, default=0,
+                    help="dense input: 0 library's choice; 1 every block computes its own Gram "
+                         "matrix; 2 Gram matrices of many blocks ahead in one launch")
     ap.add_argument("--n", type=int, default=0, help="override rows per worker (shorter epoch)")
     ap.add_argument("--seed", type=int, default=2302)
     ap.add_argument("--cpu-sample-pairs", type=int, default=-1,
@@ -165,7 +168,11 @@ def main():
         return bench_next_rows(args)
     w = workloads.CONFIGS[args.workload]
     m, n, d = w.m, (args.n or w.n), w.d
-    fused = args.apply_mode == 2 or (args.apply_mode == 0 and bool(pkg.cdgrab_plan_epoch(m, n, d)["fused_apply"]))
+    plan0 = pkg.cdgrab_plan_epoch(m, n, d, streamed=workloads.CONFIGS[args.workload].kind == "stream")
+    fused = args.apply_mode == 2 or (args.apply_mode == 0 and bool(plan0["fused_apply"]))
+    # dense input with short rows: Gram matrices of many blocks ahead in one launch
+    ahead = workloads.CONFIGS[args.workload].kind != "stream" and plan0["blocks"] >= 2 and (
+        args.gram_mode == 2 or (args.gram_mode == 0 and args.apply_mode == 0 and bool(plan0["gram_ahead"])))
     N = m * n
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
@@ -175,7 +182,7 @@ def main():
     gen_fn = gen_ctx = grads = rows_src = None
     pergrad_ms = None
     h = pkg.Handle(device=0, block_pairs=args.block_pairs, timing=1, pass1_groups=args.pass1_groups,
-                   apply_mode=args.apply_mode)
+                   apply_mode=args.apply_mode, gram_mode=args.gram_mode)
     if w.kind == "stream":
         rows_src = synth.from_workload(w, args.seed, n=n)
         gen_fn, gen_ctx = rows_src.device_callback(str(dev))
@@ -233,14 +240,19 @@ def main():
     kernels = {}
     if not args.no_profile_step:
         hp = pkg.Handle(device=0, block_pairs=args.block_pairs, timing=2, pass1_groups=args.pass1_groups,
-                        apply_mode=args.apply_mode)
+                        apply_mode=args.apply_mode, gram_mode=args.gram_mode)
         if w.kind == "softmax":
             pkg.cdgrab_pergrad(hp, Xd, yd, Wd, G)
         pkg.cdgrab_balance_epoch(hp, m, n, d, grads=grads, gen=gen_fn, gen_ctx=gen_ctx, perm_in=perm_in)
         tp = hp.timing()
         pairs = N // 2
         avg_pairs = pairs / blocks
-        if not fused:
+        if ahead:
+            # per block: its share of the batched Gram launch (rows once) and the dots + apply
+            # launch (rows of this block and of the previous one, running sum read and written)
+            per_kernel = (("gram_batched+dots_apply", tp["pass1_ms"] + tp["pass2_ms"],
+                           24.0 * avg_pairs * d + 16.0 * d),)
+        elif not fused:
             # algorithmic bytes per launch: both rows of every pair in the block (fp32) plus the
             # double running sum (read in pass 1; read and written in pass 2)
             per_kernel = (("pass1_dots_gram", tp["pass1_ms"], 8.0 * avg_pairs * d + 8.0 * d),
@@ -275,6 +287,8 @@ def main():
     # whole balancer against the roofline: 8d + 12 d / Bb bytes per example with separate passes
     # (running sum read twice, written once per block), 8d + 8 d / Bb with the fused launch
     bytes_per_example = 8.0 * d + (8.0 if fused else 12.0) * d / bb
+    if ahead:  # rows read three times (Grams ahead, then as this block and as the previous one)
+        bytes_per_example = 12.0 * d + 8.0 * d / bb
     balancer_gbs = bytes_per_example * N / (path_ms * 1e-3) / 1e9
 
     # the same epoch without the generator's cache drain (its write-back then lands in pass 1)
@@ -347,7 +361,7 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": args.workload, "m": m, "n": n, "d": d, "examples": N,
                    "block_pairs": bb, "blocks": blocks, "input": w.kind,
-                   "fused_apply": fused,
+                   "fused_apply": fused and not ahead, "gram_ahead": ahead,
                    "input_drain": bool(w.kind == "stream" and not args.no_input_drain),
                    "rows_dtype": "f32", "parallelism": "1 GPU, m workers as a batch axis"},
         "generator_ms_per_step": gen_ms, "wall_ms_per_step": wall_ms,

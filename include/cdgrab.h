@@ -46,7 +46,12 @@ typedef struct cdgrab_options {
                             apply launch after the block is resolved; 2 = inside the next
                             block's dot/Gram launch (one streaming launch per block, the
                             running sum read once per block); 0 = choose by row length  */
-    int32_t reserved;
+    int32_t gram_mode;   /* dense input only.  1 = every block computes its Gram matrix in
+                            its own dot/Gram launch; 2 = the Gram matrices of up to 512
+                            blocks are computed ahead in one launch (they depend on the
+                            rows only) and a block then costs one dots + apply launch and
+                            the resolver; 0 = choose (2 for rows up to 16 384 elements when
+                            apply_mode is 0 as well)                                      */
 } cdgrab_options;
 
 /* Event-timed durations of the last cdgrab_balance_epoch call (timing >= 1);
@@ -74,11 +79,14 @@ typedef struct cdgrab_plan {
     int32_t fused_apply;     /* 1: apply fused into the next block's launch (apply_mode 0) */
     int32_t pass1_groups;    /* workgroups of the dot/Gram pass                       */
     int32_t pass2_groups;    /* workgroups of the apply pass                          */
+    int32_t gram_ahead;      /* 1: Gram matrices computed ahead (gram_mode 0, dense input) */
+    int32_t reserved;
     int64_t workspace_bytes; /* running sum + partials (+ staging when streaming)     */
     int64_t staging_bytes;   /* staging blocks [Bb][2][d] fp32 (two when fused), 0 for dense input */
     double bytes_per_example;/* algorithmic HBM bytes per example: each row twice, plus the
                                 double running sum per block: 8d + 12 d / Bb (read twice,
-                                written once) or 8d + 8 d / Bb when fused               */
+                                written once) or 8d + 8 d / Bb when fused; 12d + 8 d / Bb
+                                with the Gram matrices computed ahead (rows read three times) */
 } cdgrab_plan;
 
 /* Generator callback for streamed input ("grads-or-generator").  It must enqueue,

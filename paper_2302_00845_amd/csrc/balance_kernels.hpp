@@ -42,10 +42,19 @@ struct RowMap {
     int32_t i0;     // worker of the block's first flattened pair
     int32_t m;
     int32_t nb;     // valid pairs in this block (<= Bb)
-    int32_t pad_;
+    int32_t dense;  // 1: the rows are those of a dense input [m][n][d] in its own order
     int64_t off[2 * kMaxBlockPairs];  // off[2 j + which]
 
     __device__ __forceinline__ const float *row(int j, int which) const { return base + off[2 * j + which]; }
+    // Same address without the table, for dense input: pair j of the block is pair
+    // k0 + (i0 + j) / m of worker (i0 + j) % m.  A per-thread j costs a memory round trip
+    // through the table and a few integer instructions this way.
+    __device__ __forceinline__ const float *dense_row(int j, int which) const {
+        const uint32_t q = (uint32_t)(i0 + j);
+        const uint32_t dk = q / (uint32_t)m;
+        const int64_t i = (int64_t)(q - dk * (uint32_t)m), k = k0 + (int64_t)dk;
+        return base + (i * n + 2 * k + which) * d;
+    }
 };
 
 // Four consecutive fp32 elements starting at element e of a row, zero beyond d or
@@ -70,6 +79,36 @@ __device__ __forceinline__ float4 load4(const float *row, int64_t e, int64_t d) 
         if (e + 1 < d) v.y = __builtin_nontemporal_load(row + e + 1);
         if (e + 2 < d) v.z = __builtin_nontemporal_load(row + e + 2);
         if (e + 3 < d) v.w = __builtin_nontemporal_load(row + e + 3);
+    }
+    return v;
+}
+
+// The same without a branch, for launches that are bound by latency rather than by
+// bytes: `row` must be readable at its first elements whether or not `have` is set,
+// out-of-range parts read the row's start instead and are replaced by zero afterwards.
+// (A load inside an `if` ends in a wait for it before the next one is issued; with
+// straight-line code all loads of a thread are in flight together.)
+template <int VW>
+__device__ __forceinline__ float4 load4_nb(const float *row, bool have, int64_t e, int64_t d) {
+    float4 v;
+    if constexpr (VW == 4) {
+        const bool in = have && e < d;
+        const float4_t t = __builtin_nontemporal_load(reinterpret_cast<const float4_t *>(row + (in ? e : 0)));
+        v = make_float4(in ? t.x : 0.f, in ? t.y : 0.f, in ? t.z : 0.f, in ? t.w : 0.f);
+    } else if constexpr (VW == 2) {
+        const bool in0 = have && e < d, in1 = have && e + 2 < d;
+        const float2_t t0 = __builtin_nontemporal_load(reinterpret_cast<const float2_t *>(row + (in0 ? e : 0)));
+        const float2_t t1 = __builtin_nontemporal_load(reinterpret_cast<const float2_t *>(row + (in1 ? e + 2 : 0)));
+        v = make_float4(in0 ? t0.x : 0.f, in0 ? t0.y : 0.f, in1 ? t1.x : 0.f, in1 ? t1.y : 0.f);
+    } else {
+        float o[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const bool in = have && e + q < d;
+            const float t = __builtin_nontemporal_load(row + (in ? e + q : 0));
+            o[q] = in ? t : 0.f;
+        }
+        v = make_float4(o[0], o[1], o[2], o[3]);
     }
     return v;
 }
@@ -112,10 +151,10 @@ struct PrevBlock {
     const int8_t *eps;   // its resolved signs
 };
 
+// `group` of `ngroups` workgroups share the tiles; the workgroup's result goes to `out`.
 template <int BB, int VW, int TE, bool APPLY>
-__global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, PrevBlock prev, double *__restrict__ r_sum,
-                                                            double *__restrict__ partials,
-                                                            int64_t ntiles)
+__device__ __forceinline__ void pass1_body(const RowMap &rm, const PrevBlock &prev, double *__restrict__ r_sum,
+                                           double *__restrict__ out, int64_t ntiles, int group, int ngroups)
 {
     using L = PartLayout<BB>;
     constexpr int RG = L::RG;
@@ -145,19 +184,33 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, PrevBlock
     const float *psrc[APPLY ? LOADS : 1];
     float psign[APPLY ? LOADS : 1];
     int lds_off[LOADS];
+    uint32_t have_mask = 0;  // bit u: load u's pair exists in this block
 #pragma unroll
     for (int u = 0; u < LOADS; ++u) {
         int rr = u * RPI + lrow;       // 0 .. 2*BB-1
         int j = rr >> 1, which = rr & 1;
-        src[u] = (j < rm.nb) ? rm.row(j, which) : nullptr;
+        // the table is read without a branch (entries of missing pairs are readable rows:
+        // zero, or those of an earlier block), so that the lookups overlap
+        src[u] = rm.row(j, which);
+        if (j < rm.nb) have_mask |= 1u << u;
         lds_off[u] = (which * TILE_FLOATS + j * STRIDE + chunk * 4) * 4;
         if constexpr (APPLY) {
             const bool have = j < prev.rm.nb;
-            psrc[u] = have ? prev.rm.row(j, which) : nullptr;
+            psrc[u] = prev.rm.row(j, which);
+            const float ej = (float)prev.eps[j];  // 64 entries, always readable
             // d_k = second - first, so the second row enters with eps and the first with -eps
-            psign[u] = have ? (float)prev.eps[j] * (which ? 1.0f : -1.0f) : 0.0f;
+            // (a missing pair enters with sign 0)
+            psign[u] = have ? ej * (which ? 1.0f : -1.0f) : 0.0f;
         }
     }
+
+    // Short rows (TE = 64: one or two tiles per workgroup, the launch is bound by latency)
+    // load without branches; the streaming configuration keeps the plain loads.  Rows of
+    // the previous block that do not exist enter with sign 0, so they need no zeroing.
+    auto tile_load = [&](const float *row, bool have, int64_t e) {
+        if constexpr (TE == 64) return load4_nb<VW>(row, have, e, d);
+        else return load4<VW>(have ? row : nullptr, e, d);
+    };
 
     double4_t acc[L::NT];
 #pragma unroll
@@ -173,18 +226,18 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, PrevBlock
     float4 prev_regs[APPLY ? LOADS : 1];
     double2 stage_s = make_double2(0.0, 0.0);
 
-    int64_t tile = blockIdx.x;
+    int64_t tile = group;
     if (tile < ntiles) {
 #pragma unroll
-        for (int u = 0; u < LOADS; ++u) stage_regs[u] = load4<VW>(src[u], tile * TE + chunk * 4, d);
+        for (int u = 0; u < LOADS; ++u) stage_regs[u] = tile_load(src[u], (have_mask >> u) & 1u, tile * TE + chunk * 4);
         if constexpr (APPLY) {
 #pragma unroll
-            for (int u = 0; u < LOADS; ++u) prev_regs[u] = load4<VW>(psrc[u], tile * TE + chunk * 4, d);
+            for (int u = 0; u < LOADS; ++u) prev_regs[u] = tile_load(psrc[u], true, tile * TE + chunk * 4);
         }
         if (tid < TE / 2) stage_s = *reinterpret_cast<const double2 *>(r_sum + tile * TE + tid * 2);
     }
     int buf = 0;
-    for (; tile < ntiles; tile += gridDim.x) {
+    for (; tile < ntiles; tile += ngroups) {
         unsigned char *stage = smem + buf * STAGE_BYTES;
 #pragma unroll
         for (int u = 0; u < LOADS; ++u)
@@ -219,13 +272,13 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, PrevBlock
         __syncthreads();
 
         // prefetch the next tile while this one is consumed
-        int64_t nxt = tile + gridDim.x;
+        int64_t nxt = tile + ngroups;
         if (nxt < ntiles) {
 #pragma unroll
-            for (int u = 0; u < LOADS; ++u) stage_regs[u] = load4<VW>(src[u], nxt * TE + chunk * 4, d);
+            for (int u = 0; u < LOADS; ++u) stage_regs[u] = tile_load(src[u], (have_mask >> u) & 1u, nxt * TE + chunk * 4);
             if constexpr (APPLY) {
 #pragma unroll
-                for (int u = 0; u < LOADS; ++u) prev_regs[u] = load4<VW>(psrc[u], nxt * TE + chunk * 4, d);
+                for (int u = 0; u < LOADS; ++u) prev_regs[u] = tile_load(psrc[u], true, nxt * TE + chunk * 4);
             }
             if (tid < TE / 2) stage_s = *reinterpret_cast<const double2 *>(r_sum + nxt * TE + tid * 2);
         }
@@ -280,7 +333,6 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, PrevBlock
 #pragma unroll
     for (int g = 0; g < RG; ++g) red[wave * PER_WAVE + L::GRAM + g * 64 + lane] = pdot[g];
     __syncthreads();
-    double *out = partials + (int64_t)blockIdx.x * L::PART;
     for (int idx = tid; idx < L::GRAM; idx += kThreads) {
         double sum = 0.0;
 #pragma unroll
@@ -296,6 +348,47 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, PrevBlock
             for (int ks = 0; ks < 4; ++ks) sum += red[w * PER_WAVE + L::GRAM + g * 64 + ks * 16 + rw];
         out[L::GRAM + tid] = sum;
     }
+}
+
+template <int BB, int VW, int TE, bool APPLY>
+__global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, PrevBlock prev, double *__restrict__ r_sum,
+                                                            double *__restrict__ partials,
+                                                            int64_t ntiles)
+{
+    pass1_body<BB, VW, TE, APPLY>(rm, prev, r_sum, partials + (int64_t)blockIdx.x * PartLayout<BB>::PART, ntiles,
+                                  (int)blockIdx.x, (int)gridDim.x);
+}
+
+// The Gram matrices of many blocks in one launch (they depend on the rows only, not on
+// the running sum or on earlier signs): blockIdx.y picks the block, whose row map is
+// read from device memory, and gridDim.x workgroups share its tiles.  The dots this
+// form also emits are taken against whatever the running sum holds and are not used.
+template <int BB, int VW, int TE>
+__global__ __launch_bounds__(kThreads) void gram_batched(const RowMap *__restrict__ maps,
+                                                         double *__restrict__ r_sum,
+                                                         double *__restrict__ partials, int64_t ntiles)
+{
+    const RowMap &rm = maps[blockIdx.y];
+    PrevBlock none;
+    none.rm.nb = 0;
+    none.eps = nullptr;
+    pass1_body<BB, VW, TE, false>(rm, none, r_sum,
+                                  partials + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * PartLayout<BB>::PART,
+                                  ntiles, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Sum over the `groups` workgroups of each block of the batched form, in group order:
+// gram_all[b][idx] = sum_g partials[(b * groups + g)][idx].
+__global__ __launch_bounds__(kThreads) void reduce_batched(const double *__restrict__ partials,
+                                                           double *__restrict__ gram_all, int part, int groups)
+{
+    const int idx = blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= part) return;
+    const double *src = partials + (int64_t)blockIdx.y * groups * part + idx;
+    double sum = 0.0;
+#pragma unroll 8
+    for (int g = 0; g < groups; ++g) sum += src[(int64_t)g * part];
+    gram_all[(int64_t)blockIdx.y * part + idx] = sum;
 }
 
 // ---------------------------------------------------------------------------
@@ -346,27 +439,58 @@ __global__ __launch_bounds__(kThreads) void reduce_partials(const double *__rest
 // keeps 64 doubles of the Gram matrix per lane in registers.
 template <int BB> constexpr int kResolveThreads = BB > 32 ? 512 : 1024;
 
-template <int BB>
-__global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const double *__restrict__ sliced, int nb,
-                                                                 int64_t k0, int32_t i0, int32_t m, int64_t half_n,
-                                                                 int8_t *__restrict__ eps_blk,
-                                                                 int8_t *__restrict__ signs_out,
-                                                                 double *__restrict__ dots_out,
-                                                                 const float *__restrict__ uniforms)
+template <int BB, bool RANDOM, int SLICES>
+__global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const double *__restrict__ gram_src,
+                                                                     int64_t gram_stride,
+                                                                     const double *__restrict__ dot_src,
+                                                                     int dot_groups, int64_t dot_stride, int nb,
+                                                                     int64_t k0, int32_t i0, int32_t m, int64_t half_n,
+                                                                     int8_t *__restrict__ eps_blk,
+                                                                     int8_t *__restrict__ signs_out,
+                                                                     double *__restrict__ dots_out,
+                                                                     const float *__restrict__ uniforms)
 {
+    // Gram tiles: sum of SLICES arrays gram_src[s * gram_stride + idx];
+    // dots: sum of dot_groups arrays dot_src[g * dot_stride + k]; both in index order.
     using L = PartLayout<BB>;
+    constexpr int NT = kResolveThreads<BB>;
+    constexpr int SUBS = (NT / BB < 16) ? NT / BB : 16;  // threads sharing one dot
     __shared__ double G[BB][BB + 1];
     __shared__ double P[BB];
-    // two consecutive entries per thread and step (16 B loads); GRAM and PART are even
-    for (int idx = 2 * threadIdx.x; idx < L::PART; idx += 2 * kResolveThreads<BB>) {
+    __shared__ double psub[BB][SUBS + 1];
+    // The dots' first sixteen groups per thread are requested before anything else and
+    // consumed after the Gram tiles: indices beyond the last group re-read it and count
+    // as zero, so that no branch separates the loads.
+    const int dk = (threadIdx.x / SUBS) % BB, dsub = threadIdx.x % SUBS;
+    double dv[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int g = dsub + u * SUBS;
+        dv[u] = dot_src[(int64_t)(g < dot_groups ? g : dot_groups - 1) * dot_stride + dk];
+    }
+    // Two consecutive entries per thread and step (16 B loads; GRAM is even).  All loads
+    // of a thread are issued before the first is used: entries beyond the end re-read
+    // entry 0 and are dropped.
+    constexpr int ITER = (L::GRAM + 2 * NT - 1) / (2 * NT);
+    double2 raw[ITER][SLICES];
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int idx = 2 * (int)threadIdx.x + it * 2 * NT;
+        const int idc = idx < L::GRAM ? idx : 0;
+#pragma unroll
+        for (int sl = 0; sl < SLICES; ++sl)
+            raw[it][sl] = *reinterpret_cast<const double2 *>(gram_src + (int64_t)sl * gram_stride + idc);
+    }
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+        const int idx = 2 * (int)threadIdx.x + it * 2 * NT;
+        if (idx >= L::GRAM) continue;
         double2 val = make_double2(0.0, 0.0);
 #pragma unroll
-        for (int s = 0; s < kReduceSlices; ++s) {
-            const double2 v = *reinterpret_cast<const double2 *>(sliced + (int64_t)s * L::PART + idx);
-            val.x += v.x;
-            val.y += v.y;
+        for (int sl = 0; sl < SLICES; ++sl) {
+            val.x += raw[it][sl].x;
+            val.y += raw[it][sl].y;
         }
-        if (idx >= L::GRAM) { P[idx - L::GRAM] = val.x; P[idx - L::GRAM + 1] = val.y; continue; }
         const int tile = idx >> 8, v = (idx >> 6) & 3, ln = idx & 63;
         // tiles are stored row group by row group, upper triangle only: (0,0), (0,1), .., (1,1), ..
         int tg = 0, th = tile;
@@ -381,6 +505,30 @@ __global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const doubl
             if (th != tg) G[16 * th + j][16 * tg + i] = x;
         }
     }
+    if (threadIdx.x < BB * SUBS) {
+        double sum = 0.0;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sum += (dsub + u * SUBS < dot_groups) ? dv[u] : 0.0;
+        // (more than 16 * SUBS groups: the rest in further batches of sixteen loads)
+        for (int g0 = dsub + 16 * SUBS; g0 < dot_groups; g0 += 16 * SUBS) {
+            double v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int g = g0 + u * SUBS;
+                v[u] = dot_src[(int64_t)(g < dot_groups ? g : dot_groups - 1) * dot_stride + dk];
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) sum += (g0 + u * SUBS < dot_groups) ? v[u] : 0.0;
+        }
+        psub[dk][dsub] = sum;
+    }
+    __syncthreads();
+    if (threadIdx.x < BB) {
+        double sum = 0.0;
+#pragma unroll
+        for (int q = 0; q < SUBS; ++q) sum += psub[threadIdx.x][q];
+        P[threadIdx.x] = sum;
+    }
     __syncthreads();
     if (threadIdx.x >= 64) return;
     const int lane = threadIdx.x;
@@ -389,8 +537,6 @@ __global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const doubl
 #pragma unroll
     for (int j = 0; j < BB; ++j) col[j] = (lane < BB) ? G[lane][j] : 0.0;
     double t = (lane < nb) ? P[lane] : 0.0;
-    double my_t = 0.0;
-    int my_eps = 0;
     // flattened pair of this lane -> (worker, pair) slot of the [m][n/2] arrays
     int64_t slot = 0;
     if (lane < nb) {
@@ -401,22 +547,21 @@ __global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const doubl
     // randomized rule (PairBalance's RandomizedBalance subroutine, Sec. 3.2): with
     // c = z1 - z2 = -d, the first row gets +1 with probability p = (1 - <r,c>)/2 =
     // (1 + t)/2, so the exported sign (of the second row) is -1 when u < p.
-    const float my_u = (uniforms && lane < nb) ? uniforms[slot] : 0.f;
+    const float my_u = (RANDOM && lane < nb) ? uniforms[slot] : 0.f;
+    auto rule = [&](double tv) { return RANDOM ? !((double)my_u < 0.5 * (1.0 + tv)) : (tv <= 0.0); };
+    // Every lane applies the rule to its own t at every step; a wave-wide vote turns
+    // lane j's answer into a scalar.  Lane k is updated at steps j < k only, so after
+    // the loop its t is the resolved dot of pair k and the rule on it is pair k's sign.
 #pragma unroll
     for (int j = 0; j < BB; ++j) {
         if (j < nb) {  // uniform
-            const int lo = __builtin_amdgcn_readlane(__double2loint(t), j);
-            const int hi = __builtin_amdgcn_readlane(__double2hiint(t), j);
-            const double tj = __hiloint2double(hi, lo);
-            int eps = (tj <= 0.0) ? 1 : -1;
-            if (uniforms) {
-                const float uj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_u), j));
-                eps = ((double)uj < 0.5 * (1.0 + tj)) ? -1 : 1;
-            }
-            if (lane == j) { my_t = tj; my_eps = eps; }
-            if (lane > j) t += (double)eps * col[j];
+            const bool plus_j = (__ballot(rule(t)) >> j) & 1ull;
+            const double cj = plus_j ? col[j] : -col[j];
+            if (lane > j) t += cj;
         }
     }
+    const double my_t = t;
+    const int my_eps = rule(t) ? 1 : -1;
     if (lane < nb) {
         eps_blk[lane] = (int8_t)my_eps;
         signs_out[slot] = (int8_t)my_eps;
@@ -482,9 +627,10 @@ __global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const i
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
         const int j = grp * PER + q;
+        // (offsets of missing pairs are readable rows: zero, or those of an earlier block)
         const bool have = FULL || j < rm.nb;
-        a[q] = load4<VW>(have ? rm.row(j, 0) : nullptr, e, d);
-        b[q] = load4<VW>(have ? rm.row(j, 1) : nullptr, e, d);
+        a[q] = load4_nb<VW>(rm.row(j, 0), have, e, d);
+        b[q] = load4_nb<VW>(rm.row(j, 1), have, e, d);
     }
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
@@ -504,6 +650,89 @@ __global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const i
 #pragma unroll
         for (int g = 0; g < kSplitGroups; ++g) sum += part[g][threadIdx.x];
         r_sum[mine] = r_old + sum;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Short rows with the Gram matrices computed ahead (gram_batched): what is left on the
+// chain of a block is  r += sum_k eps_k d_k  over the PREVIOUS block, and the dots
+// <r, d_k> of this block against the result.  Same thread layout as
+// pass2_apply_split: a workgroup owns 64 elements, group g of 16 threads takes the
+// pairs g*PER .. g*PER+PER-1 of either block.  DENSE: row addresses by arithmetic
+// (RowMap::dense_row) instead of through the offset table.  Each workgroup writes its share of the
+// BB dots to dot_partials[blockIdx.x][BB]; the resolver adds the workgroups in order.
+template <int BB, int VW, bool DENSE>
+__global__ __launch_bounds__(kThreads) void dots_apply_split(RowMap rm, PrevBlock prev,
+                                                             double *__restrict__ r_sum,
+                                                             double *__restrict__ dot_partials)
+{
+    __shared__ double part[kSplitGroups][kSplitElems];
+    __shared__ double rnew[kSplitElems];
+    const int64_t d = rm.d;
+    constexpr int QUADS = kThreads / kSplitGroups;  // 16 threads, four elements each
+    const int quad = threadIdx.x % QUADS, grp = threadIdx.x / QUADS;
+    const int64_t e = (int64_t)blockIdx.x * kSplitElems + quad * 4;
+    const int64_t mine = (int64_t)blockIdx.x * kSplitElems + threadIdx.x;
+    // all loads of the workgroup are requested up front: the launch is latency-bound
+    const double r_old = (threadIdx.x < kSplitElems) ? r_sum[mine] : 0.0;  // padded to a multiple of 128
+    constexpr int PER = BB / kSplitGroups;
+    float4 pa[PER], pb[PER], ca[PER], cb[PER];
+    double sg[PER];
+    // Offsets of missing pairs are zero, so every row pointer is valid: no branch stands
+    // between the offset loads and the row loads, and a missing pair of the previous block
+    // enters with sign 0 (a missing pair of this block yields a dot nobody reads).
+    const float *rp[PER][4];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int j = grp * PER + q;
+        // (a pair beyond the block's or the epoch's end maps to the block's first pair: readable)
+        const int jp = j < prev.rm.nb ? j : 0, jc = j < rm.nb ? j : 0;
+        rp[q][0] = DENSE ? prev.rm.dense_row(jp, 0) : prev.rm.row(j, 0);
+        rp[q][1] = DENSE ? prev.rm.dense_row(jp, 1) : prev.rm.row(j, 1);
+        rp[q][2] = DENSE ? rm.dense_row(jc, 0) : rm.row(j, 0);
+        rp[q][3] = DENSE ? rm.dense_row(jc, 1) : rm.row(j, 1);
+    }
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int j = grp * PER + q;
+        pa[q] = load4_nb<VW>(rp[q][0], true, e, d);
+        pb[q] = load4_nb<VW>(rp[q][1], true, e, d);
+        ca[q] = load4_nb<VW>(rp[q][2], true, e, d);
+        cb[q] = load4_nb<VW>(rp[q][3], true, e, d);
+        const double ej = (double)prev.eps[j];  // 64 entries, always readable
+        sg[q] = (j < prev.rm.nb) ? ej : 0.0;
+    }
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        acc[0] = __builtin_fma(sg[q], (double)pb[q].x - (double)pa[q].x, acc[0]);
+        acc[1] = __builtin_fma(sg[q], (double)pb[q].y - (double)pa[q].y, acc[1]);
+        acc[2] = __builtin_fma(sg[q], (double)pb[q].z - (double)pa[q].z, acc[2]);
+        acc[3] = __builtin_fma(sg[q], (double)pb[q].w - (double)pa[q].w, acc[3]);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) part[grp][quad * 4 + q] = acc[q];
+    __syncthreads();
+    if (threadIdx.x < kSplitElems) {
+        double sum = 0.0;
+#pragma unroll
+        for (int g = 0; g < kSplitGroups; ++g) sum += part[g][threadIdx.x];
+        const double r = r_old + sum;  // elements beyond d load as zero, so the padding stays zero
+        r_sum[mine] = r;
+        rnew[threadIdx.x] = r;
+    }
+    __syncthreads();
+    const double r0 = rnew[quad * 4], r1 = rnew[quad * 4 + 1], r2 = rnew[quad * 4 + 2], r3 = rnew[quad * 4 + 3];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        double p = r0 * ((double)cb[q].x - (double)ca[q].x);
+        p = __builtin_fma(r1, (double)cb[q].y - (double)ca[q].y, p);
+        p = __builtin_fma(r2, (double)cb[q].z - (double)ca[q].z, p);
+        p = __builtin_fma(r3, (double)cb[q].w - (double)ca[q].w, p);
+        // the 16 threads of a group are 16 consecutive lanes
+#pragma unroll
+        for (int off = 1; off < QUADS; off <<= 1) p += __shfl_xor(p, off, 64);
+        if (quad == 0) dot_partials[(int64_t)blockIdx.x * BB + grp * PER + q] = p;
     }
 }
 
@@ -528,6 +757,46 @@ __global__ void fill_zero_f64(double *p, int64_t count) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (; i < count; i += stride) p[i] = 0.0;
+}
+
+// Row maps of `count` consecutive blocks of a dense input [m][n][d], starting at
+// flattened pair first_pair: block b holds the pairs first_pair + b*bb .. (up to
+// total_pairs).  With center_off >= 0 the input is n single rows, each paired with
+// the row at element offset center_off (see RowMap).  One thread per (block, pair).
+__global__ __launch_bounds__(kMaxBlockPairs) void fill_row_maps(RowMap *__restrict__ maps, const float *base,
+                                                                int64_t m, int64_t n, int64_t d, int bb,
+                                                                int64_t first_pair, int64_t total_pairs,
+                                                                int64_t center_off, int use_center)
+{
+    RowMap &rm = maps[blockIdx.x];
+    const int j = threadIdx.x;
+    const int64_t p0 = first_pair + (int64_t)blockIdx.x * bb;
+    const int64_t left = total_pairs - p0;
+    const int nb = (int)(left < bb ? left : bb);
+    if (j == 0) {
+        rm.base = base;
+        rm.d = d;
+        rm.n = n;
+        rm.k0 = p0 / m;
+        rm.i0 = (int32_t)(p0 - (p0 / m) * m);
+        rm.m = (int32_t)m;
+        rm.nb = nb;
+        rm.dense = use_center ? 0 : 1;
+    }
+    int64_t o0 = 0, o1 = 0;
+    if (j < nb) {
+        const int64_t p = p0 + j;
+        if (use_center) {
+            o0 = p * d;
+            o1 = center_off;
+        } else {
+            const int64_t k = p / m, i = p - k * m;
+            o0 = (i * n + 2 * k) * d;
+            o1 = o0 + d;
+        }
+    }
+    rm.off[2 * j] = o0;
+    rm.off[2 * j + 1] = o1;
 }
 
 __global__ void export_running_sum(const double *__restrict__ r_sum, int64_t d, float *__restrict__ r32,

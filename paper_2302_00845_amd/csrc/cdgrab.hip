@@ -39,6 +39,7 @@ struct cdgrab_handle {
     int timing = 0;
     int pass1_groups_opt = 0;
     int apply_mode = 0;  // 0 choose by row length, 1 separate apply launch, 2 apply fused into the next block's launch
+    int gram_mode = 0;   // 0 choose, 1 each block's Gram in its own launch, 2 Grams of many blocks ahead in one launch
     int num_cu = 256;
     std::string err;
 
@@ -53,6 +54,9 @@ struct cdgrab_handle {
     int32_t *train_perm = nullptr; int64_t train_perm_cap = 0;  // spare [m][n] order of the multi-epoch driver
     int8_t *train_signs = nullptr; int64_t train_signs_cap = 0; // its [m][n/2] signs when the caller wants none
     double *herd_ws = nullptr; int64_t herd_cap = 0;      // herding evaluator: segment sums, starts, mean
+    double *gram_all = nullptr; int64_t gram_all_cap = 0; // Grams-ahead form: reduced tiles of up to kGramBatch blocks
+    double *dot_partials = nullptr; int64_t dot_partials_cap = 0;  // its per-workgroup dots of one block
+    RowMap *maps = nullptr; int64_t maps_cap = 0;         // its row maps (device)
     float *staging = nullptr;  int64_t staging_cap = 0;   // floats: two staging chunks (the fused pass reads the previous block too)
 
     std::vector<hipEvent_t> event_pool;
@@ -104,6 +108,16 @@ int pick_block_pairs(int64_t pairs, int64_t d, int32_t requested) {
 // two lean ones.
 bool fuse_apply_by_default(int64_t d) { return d <= ((int64_t)1 << 21); }
 
+// Dense input with short rows: a block is bound by its chain of launches, so the Gram
+// matrices (which depend on the rows only) are taken off the chain: one launch computes
+// them for up to kGramBatch blocks, and a block then costs a dots + apply launch and the
+// resolver.  Measured on MI355X (m = 16, n = 3750): see the crossover table in the design notes.
+constexpr int64_t kGramBatch = 512;
+constexpr int64_t kGramAheadMaxD = 16384;
+bool gram_ahead_by_default(int64_t d, int64_t blocks, bool streamed) {
+    return !streamed && blocks >= 2 && d <= kGramAheadMaxD;
+}
+
 int part_size(int bb) {
     return bb == 64 ? PartLayout<64>::PART : bb == 32 ? PartLayout<32>::PART : PartLayout<16>::PART;
 }
@@ -134,6 +148,10 @@ int plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs, int32_t str
                             (int64_t)plan->pass1_groups * part_size(plan->block_pairs) * 8 +
                             plan->staging_bytes;
     plan->bytes_per_example = 8.0 * (double)d + (fused ? 8.0 : 12.0) * (double)d / plan->block_pairs;
+    plan->gram_ahead = gram_ahead_by_default(d, plan->blocks, streamed != 0) ? 1 : 0;
+    plan->reserved = 0;
+    // rows read once for the Grams and twice on the chain (as this block, then as the previous one)
+    if (plan->gram_ahead) plan->bytes_per_example = 12.0 * (double)d + 8.0 * (double)d / plan->block_pairs;
     return CDGRAB_OK;
 }
 
@@ -220,8 +238,78 @@ void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
 }
 template <int BB>
 void launch_resolve(cdgrab_handle *h, const RowMap &rm, int8_t *signs_out, double *dots_out) {
-    hipLaunchKernelGGL((resolve_signs<BB>), dim3(1), dim3(kResolveThreads<BB>), 0, h->stream, h->reduced, rm.nb,
-                       rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out, h->uniforms);
+    // Gram tiles and dots both come from the kReduceSlices slice sums
+    constexpr int part = PartLayout<BB>::PART;
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(1), dim3(kResolveThreads<BB>), 0, h->stream, h->reduced,
+                           (int64_t)part, h->reduced + PartLayout<BB>::GRAM, kReduceSlices, (int64_t)part, rm.nb,
+                           rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out, h->uniforms);
+    };
+    if (h->uniforms) launch(resolve_signs<BB, true, kReduceSlices>);
+    else launch(resolve_signs<BB, false, kReduceSlices>);
+}
+
+// Grams-ahead form of one block: dots + apply of the previous block, then the resolver
+// on the block's reduced Gram tiles and the per-workgroup dots.
+template <int BB>
+int run_block_ahead(cdgrab_handle *h, const RowMap &rm, const PrevBlock &prev, const cdgrab_plan &plan,
+                    const double *gram, int8_t *signs_out, double *dots_out) {
+    const unsigned groups = (unsigned)((rm.d + kSplitElems - 1) / kSplitElems);
+    MARK(h, 2, kPass1);
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(groups), dim3(kThreads), 0, h->stream, rm, prev, h->r_sum, h->dot_partials);
+    };
+    if (rm.dense) {
+        switch (plan.vector_width) {
+            case 4: launch(dots_apply_split<BB, 4, true>); break;
+            case 2: launch(dots_apply_split<BB, 2, true>); break;
+            default: launch(dots_apply_split<BB, 1, true>); break;
+        }
+    } else {
+        switch (plan.vector_width) {
+            case 4: launch(dots_apply_split<BB, 4, false>); break;
+            case 2: launch(dots_apply_split<BB, 2, false>); break;
+            default: launch(dots_apply_split<BB, 1, false>); break;
+        }
+    }
+    MARK(h, 2, kResolve);
+    auto resolve = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(1), dim3(kResolveThreads<BB>), 0, h->stream, gram, (int64_t)0,
+                           h->dot_partials, (int)groups, (int64_t)BB, rm.nb, rm.k0, rm.i0, rm.m, rm.n / 2,
+                           h->eps_blk, signs_out, dots_out, h->uniforms);
+    };
+    if (h->uniforms) resolve(resolve_signs<BB, true, 1>);
+    else resolve(resolve_signs<BB, false, 1>);
+    HIP_TRY(h, hipGetLastError());
+    return CDGRAB_OK;
+}
+
+// Gram tiles of `count` blocks (row maps already in h->maps) into h->gram_all.
+template <int BB>
+int run_grams_ahead(cdgrab_handle *h, int64_t d, const cdgrab_plan &plan, int64_t count, int groups) {
+    constexpr int part = PartLayout<BB>::PART;
+    const dim3 grid((unsigned)groups, (unsigned)count), block(kThreads);
+    MARK(h, 2, kPass1);
+    if (plan.tile_elems == 128) {
+        const int64_t ntiles = (d + 127) / 128;
+        switch (plan.vector_width) {
+            case 4: hipLaunchKernelGGL((gram_batched<BB, 4, 128>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
+            case 2: hipLaunchKernelGGL((gram_batched<BB, 2, 128>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
+            default: hipLaunchKernelGGL((gram_batched<BB, 1, 128>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
+        }
+    } else {
+        const int64_t ntiles = (d + 63) / 64;
+        switch (plan.vector_width) {
+            case 4: hipLaunchKernelGGL((gram_batched<BB, 4, 64>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
+            case 2: hipLaunchKernelGGL((gram_batched<BB, 2, 64>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
+            default: hipLaunchKernelGGL((gram_batched<BB, 1, 64>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
+        }
+    }
+    MARK(h, 2, kReduce);
+    hipLaunchKernelGGL(reduce_batched, dim3((part + kThreads - 1) / kThreads, (unsigned)count), block, 0, h->stream,
+                       h->partials, h->gram_all, part, groups);
+    HIP_TRY(h, hipGetLastError());
+    return CDGRAB_OK;
 }
 
 // One block: dots + Gram (with the previous block applied in the same launch when
@@ -282,6 +370,7 @@ int cdgrab_create(cdgrab_handle **out, const cdgrab_options *opt) {
     if (o.pass1_groups < 0 || o.pass1_groups > 65536)
         return fail(nullptr, CDGRAB_EINVAL, "pass1_groups out of range");
     if (o.apply_mode < 0 || o.apply_mode > 2) return fail(nullptr, CDGRAB_EINVAL, "apply_mode must be 0, 1 or 2");
+    if (o.gram_mode < 0 || o.gram_mode > 2) return fail(nullptr, CDGRAB_EINVAL, "gram_mode must be 0, 1 or 2");
     int count = 0;
     hipError_t e = hipGetDeviceCount(&count);
     if (e != hipSuccess || o.device < 0 || o.device >= count)
@@ -295,6 +384,7 @@ int cdgrab_create(cdgrab_handle **out, const cdgrab_options *opt) {
     h->timing = o.timing;
     h->pass1_groups_opt = o.pass1_groups;
     h->apply_mode = o.apply_mode;
+    h->gram_mode = o.gram_mode;
     hipDeviceProp_t prop;
     if (hipSetDevice(h->device) == hipSuccess && hipGetDeviceProperties(&prop, h->device) == hipSuccess)
         h->num_cu = prop.multiProcessorCount;
@@ -318,6 +408,9 @@ int cdgrab_destroy(cdgrab_handle *h) {
     if (h->train_signs) (void)hipFree(h->train_signs);
     if (h->zero_row) (void)hipFree(h->zero_row);
     if (h->staging) (void)hipFree(h->staging);
+    if (h->gram_all) (void)hipFree(h->gram_all);
+    if (h->dot_partials) (void)hipFree(h->dot_partials);
+    if (h->maps) (void)hipFree(h->maps);
     delete h;
     return CDGRAB_OK;
 }
@@ -416,6 +509,24 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     const bool fused = h->apply_mode == 2 || (h->apply_mode == 0 && fuse_apply_by_default(d));
     const int64_t staging_chunk = chunk_pairs * 2 * d;  // floats per staging chunk
     if (streamed) { rc = ensure(h, h->staging, h->staging_cap, (fused ? 2 : 1) * staging_chunk); if (rc) return rc; }
+    // Grams ahead (dense input): asked for, or chosen for short rows when the caller left both choices open
+    const bool ahead = !streamed && plan.blocks >= 2 &&
+                       (h->gram_mode == 2 || (h->gram_mode == 0 && h->apply_mode == 0 && plan.gram_ahead));
+    const int64_t batch = std::min<int64_t>(plan.blocks, kGramBatch);
+    int gram_groups = 1;
+    if (ahead) {
+        // enough workgroups to fill the chip, at least one tile each
+        const int64_t ntiles = (d + plan.tile_elems - 1) / plan.tile_elems;
+        gram_groups = (int)std::max<int64_t>(1, std::min<int64_t>(ntiles, (8 * h->num_cu + batch - 1) / batch));
+        rc = ensure(h, h->partials, h->partials_cap, batch * gram_groups * part_size(bb));
+        if (rc) return rc;
+        rc = ensure(h, h->gram_all, h->gram_all_cap, batch * part_size(bb));
+        if (rc) return rc;
+        rc = ensure(h, h->dot_partials, h->dot_partials_cap, (d + kSplitElems - 1) / kSplitElems * bb);
+        if (rc) return rc;
+        rc = ensure(h, h->maps, h->maps_cap, batch);
+        if (rc) return rc;
+    }
 
     h->marks.clear();
     h->events_used = 0;
@@ -425,55 +536,92 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                        h->stream, h->r_sum, h->r_cap);
 
     RowMap rm;
-    rm.d = d; rm.m = (int32_t)m; rm.n = n; rm.pad_ = 0;
+    rm.d = d; rm.m = (int32_t)m; rm.n = n; rm.dense = (!streamed && !center_row) ? 1 : 0;
+    rm.k0 = 0; rm.i0 = 0; rm.nb = 0;  // (a copy of this map stands in for "no previous block": its rows must be readable)
     rm.base = grads;
     for (int64_t &o : rm.off) o = 0;
-    const int64_t chunk = streamed ? chunk_pairs : plan.pairs;
+    const int64_t center_off =
+        center_row ? (int64_t)((reinterpret_cast<intptr_t>(center_row) - reinterpret_cast<intptr_t>(grads)) /
+                               (intptr_t)sizeof(float))
+                   : 0;
+    // row offsets of the block of flattened pairs p0 .. p0+nb-1 (dense input), or of a
+    // staging chunk's rows [2 q], [2 q + 1]
+    auto set_block = [&](int64_t p0, int64_t nb, const float *stage_base) {
+        rm.k0 = p0 / m;
+        rm.i0 = (int32_t)(p0 - rm.k0 * m);
+        rm.nb = (int32_t)nb;
+        if (stage_base) rm.base = stage_base;
+        for (int j = 0; j < rm.nb; ++j) {
+            if (stage_base) {
+                rm.off[2 * j] = (int64_t)(2 * j) * d;
+            } else if (center_row) {
+                rm.off[2 * j] = (p0 + j) * d;
+                rm.off[2 * j + 1] = center_off;
+                continue;
+            } else {
+                const int64_t p = p0 + j, k = p / m, i = p - k * m;
+                rm.off[2 * j] = (i * n + 2 * k) * d;
+            }
+            rm.off[2 * j + 1] = rm.off[2 * j] + d;
+        }
+    };
     PrevBlock prev;
     prev.eps = h->eps_blk;
+    prev.rm = rm;
+    prev.rm.nb = 0;
     bool have_prev = false;
-    int64_t chunk_index = 0;
-    for (int64_t first = 0; first < plan.pairs; first += chunk, ++chunk_index) {
-        const int64_t cnt = std::min<int64_t>(chunk, plan.pairs - first);
-        // with the fused pass the previous block's rows must outlive this chunk's staging
-        float *stage_buf = h->staging + ((fused && (chunk_index & 1)) ? staging_chunk : 0);
-        if (streamed) {
-            MARK(h, 1, kGen);
-            int grc = gen(gen_ctx, first, cnt, stage_buf, h->stream);
-            if (grc != 0)
-                return fail(h, CDGRAB_EGEN, "generator callback returned %d at pair %lld", grc,
-                            (long long)first);
-        }
-        for (int64_t p0 = first; p0 < first + cnt; p0 += bb) {
-            rm.k0 = p0 / m;
-            rm.i0 = (int32_t)(p0 - rm.k0 * m);
-            rm.nb = (int32_t)std::min<int64_t>(bb, first + cnt - p0);
-            if (streamed) rm.base = stage_buf + (p0 - first) * 2 * d;
-            for (int j = 0; j < rm.nb; ++j) {
-                if (streamed) {
-                    rm.off[2 * j] = (int64_t)(2 * j) * d;
-                } else if (center_row) {
-                    rm.off[2 * j] = (p0 + j) * d;
-                    rm.off[2 * j + 1] = (int64_t)((reinterpret_cast<intptr_t>(center_row) -
-                                                   reinterpret_cast<intptr_t>(grads)) / (intptr_t)sizeof(float));
-                    continue;
-                } else {
-                    const int64_t p = p0 + j, k = p / m, i = p - k * m;
-                    rm.off[2 * j] = (i * n + 2 * k) * d;
-                }
-                rm.off[2 * j + 1] = rm.off[2 * j] + d;
-            }
+    if (ahead) {
+        // Gram matrices of up to kGramBatch blocks in one launch, then the chain of blocks
+        for (int64_t b0 = 0; b0 < plan.blocks; b0 += batch) {
+            const int64_t count = std::min<int64_t>(batch, plan.blocks - b0);
             MARK(h, 1, kBalance);
-            const PrevBlock *pp = (fused && have_prev) ? &prev : nullptr;
-            rc = (bb == 64)   ? run_block_vw<64>(h, rm, pp, !fused, plan, signs_out, dots_out)
-                 : (bb == 32) ? run_block_vw<32>(h, rm, pp, !fused, plan, signs_out, dots_out)
-                              : run_block_vw<16>(h, rm, pp, !fused, plan, signs_out, dots_out);
+            hipLaunchKernelGGL(fill_row_maps, dim3((unsigned)count), dim3(kMaxBlockPairs), 0, h->stream, h->maps,
+                               grads, m, n, d, bb, b0 * bb, plan.pairs, center_off, center_row ? 1 : 0);
+            rc = (bb == 64)   ? run_grams_ahead<64>(h, d, plan, count, gram_groups)
+                 : (bb == 32) ? run_grams_ahead<32>(h, d, plan, count, gram_groups)
+                              : run_grams_ahead<16>(h, d, plan, count, gram_groups);
             if (rc) return rc;
-            prev.rm = rm;
-            have_prev = true;
+            for (int64_t b = 0; b < count; ++b) {
+                const int64_t p0 = (b0 + b) * bb;
+                set_block(p0, std::min<int64_t>(bb, plan.pairs - p0), nullptr);
+                const double *gram = h->gram_all + b * part_size(bb);
+                rc = (bb == 64)   ? run_block_ahead<64>(h, rm, prev, plan, gram, signs_out, dots_out)
+                     : (bb == 32) ? run_block_ahead<32>(h, rm, prev, plan, gram, signs_out, dots_out)
+                                  : run_block_ahead<16>(h, rm, prev, plan, gram, signs_out, dots_out);
+                if (rc) return rc;
+                prev.rm = rm;
+                have_prev = true;
+            }
+        }
+    } else {
+        const int64_t chunk = streamed ? chunk_pairs : plan.pairs;
+        int64_t chunk_index = 0;
+        for (int64_t first = 0; first < plan.pairs; first += chunk, ++chunk_index) {
+            const int64_t cnt = std::min<int64_t>(chunk, plan.pairs - first);
+            // with the fused pass the previous block's rows must outlive this chunk's staging
+            float *stage_buf = h->staging + ((fused && (chunk_index & 1)) ? staging_chunk : 0);
+            if (streamed) {
+                MARK(h, 1, kGen);
+                int grc = gen(gen_ctx, first, cnt, stage_buf, h->stream);
+                if (grc != 0)
+                    return fail(h, CDGRAB_EGEN, "generator callback returned %d at pair %lld", grc,
+                                (long long)first);
+            }
+            for (int64_t p0 = first; p0 < first + cnt; p0 += bb) {
+                set_block(p0, std::min<int64_t>(bb, first + cnt - p0),
+                          streamed ? stage_buf + (p0 - first) * 2 * d : nullptr);
+                MARK(h, 1, kBalance);
+                const PrevBlock *pp = (fused && have_prev) ? &prev : nullptr;
+                rc = (bb == 64)   ? run_block_vw<64>(h, rm, pp, !fused, plan, signs_out, dots_out)
+                     : (bb == 32) ? run_block_vw<32>(h, rm, pp, !fused, plan, signs_out, dots_out)
+                                  : run_block_vw<16>(h, rm, pp, !fused, plan, signs_out, dots_out);
+                if (rc) return rc;
+                prev.rm = rm;
+                have_prev = true;
+            }
         }
     }
-    if (fused && have_prev) {  // the last block has no successor to apply it
+    if ((fused || ahead) && have_prev) {  // the last block has no successor to apply it
         MARK(h, 1, kBalance);
         rc = (bb == 64)   ? apply_block_vw<64>(h, prev.rm, plan)
              : (bb == 32) ? apply_block_vw<32>(h, prev.rm, plan)
@@ -493,8 +641,8 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     MARK(h, 1, -1);
     HIP_TRY(h, hipGetLastError());
     h->last = cdgrab_timing{};
-    h->last.blocks = streamed ? ((plan.pairs / chunk) * ((chunk + bb - 1) / bb) +
-                                 ((plan.pairs % chunk) + bb - 1) / bb)
+    h->last.blocks = streamed ? ((plan.pairs / chunk_pairs) * ((chunk_pairs + bb - 1) / bb) +
+                                 ((plan.pairs % chunk_pairs) + bb - 1) / bb)
                               : plan.blocks;
     h->last.block_pairs = bb;
     h->last.pass1_groups = plan.pass1_groups;
