@@ -63,6 +63,11 @@ def test_plan_epoch_headline_shapes(p):
     c2 = p.cdgrab_plan_epoch(16, 3750, 7850)
     assert c2["pairs"] == 30000 and c2["block_pairs"] == 64 and c2["blocks"] == 469 and c2["vector_width"] == 2
     assert c2["staging_bytes"] == 0
+    # short dense rows: Gram matrices ahead, rows read three times
+    assert c2["gram_ahead"] == 1 and c2["bytes_per_example"] == 12 * 7850 + 8 * 7850 / 64
+    assert c4["gram_ahead"] == 0 and c3["gram_ahead"] == 0
+    assert p.cdgrab_plan_epoch(16, 3750, 7850, streamed=True)["gram_ahead"] == 0
+    assert p.cdgrab_plan_epoch(4, 64, 100_000)["gram_ahead"] == 0
     odd = p.cdgrab_plan_epoch(3, 4, 1001, base_align=4)
     assert odd["vector_width"] == 1 and odd["block_pairs"] == 16 and odd["blocks"] == 1
     assert p.cdgrab_plan_epoch(1, 2, 1)["pass1_groups"] == 1

@@ -21,9 +21,9 @@ def lib():
     return p
 
 
-def run_epoch(p, z, perm_in=None, block_pairs=0, pass1_groups=0, apply_mode=0):
+def run_epoch(p, z, perm_in=None, block_pairs=0, pass1_groups=0, apply_mode=0, gram_mode=0):
     m, n, d = z.shape
-    h = p.Handle(block_pairs=block_pairs, pass1_groups=pass1_groups, apply_mode=apply_mode)
+    h = p.Handle(block_pairs=block_pairs, pass1_groups=pass1_groups, apply_mode=apply_mode, gram_mode=gram_mode)
     zt = torch.from_numpy(z).cuda()
     pt = torch.from_numpy(perm_in).cuda() if perm_in is not None else None
     out = p.cdgrab_balance_epoch(h, m, n, d, grads=zt, perm_in=pt, want_r32=True, want_r64=True,
@@ -92,6 +92,37 @@ def test_fused_and_separate_passes_agree(lib, m, n, d, bb):
     z = workloads.heavy_rows(m * n, m, n, d)
     check_epoch(z, run_epoch(lib, z, block_pairs=bb, apply_mode=2))
     check_epoch(z, run_epoch(lib, z, block_pairs=bb, apply_mode=1))
+
+
+@pytest.mark.parametrize("m,n,d,bb", [(4, 64, 1024, 16), (3, 50, 777, 32), (8, 40, 65536 + 12, 32),
+                                      (16, 30, 130, 64), (2, 70, 4100, 0), (5, 6, 3, 16), (1, 4, 1, 0)])
+def test_grams_ahead_and_per_block_agree(lib, m, n, d, bb):
+    """The Gram matrices do not depend on the running sum, so computing them for many
+    blocks ahead (one launch) and computing each inside its block's own launch are the
+    same computation: bit-identical on exact input, both within the oracle's tolerances on
+    heavy-tailed rows.  (The long-row case forces the ahead form where it is not the default.)"""
+    zi = workloads.integer_rows(m + n + 1, m, n, d, 6)
+    perm = workloads.random_perms(2, m, n)
+    a = run_epoch(lib, zi, perm_in=perm, block_pairs=bb, gram_mode=2)
+    b = run_epoch(lib, zi, perm_in=perm, block_pairs=bb, gram_mode=1)
+    for k in ("signs", "perm", "r64", "dots"):
+        assert np.array_equal(a[k], b[k]), k
+    check_epoch(zi, a, perm, expect_exact_signs=True)
+    z = workloads.heavy_rows(m * n + 1, m, n, d)
+    check_epoch(z, run_epoch(lib, z, block_pairs=bb, gram_mode=2))
+    check_epoch(z, run_epoch(lib, z, block_pairs=bb, gram_mode=1))
+
+
+def test_grams_ahead_over_several_batches(lib):
+    """More blocks than one ahead-launch covers (512): the last block of a batch is the
+    previous block of the next batch's first."""
+    m, n, d = 3, 2 * 16 * 180, 37                     # 8640 pairs = 540 blocks of 16
+    zi = workloads.integer_rows(77, m, n, d, 3)
+    a = run_epoch(lib, zi, block_pairs=16, gram_mode=2)
+    b = run_epoch(lib, zi, block_pairs=16, gram_mode=1)
+    for k in ("signs", "perm", "r64", "dots"):
+        assert np.array_equal(a[k], b[k]), k
+    check_epoch(zi, a, expect_exact_signs=True)
 
 
 def test_unaligned_base_pointer(lib):
