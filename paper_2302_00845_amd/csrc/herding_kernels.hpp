@@ -29,7 +29,7 @@ __device__ __forceinline__ void herding_step_sum(const float *__restrict__ z, co
 #pragma unroll 8
     for (int64_t i = 0; i < sh.m; ++i) {
         const int64_t id = perm ? (int64_t)perm[i * sh.n + j] : j;
-        const float4 x = load4<VW>(z + (i * sh.n + id) * sh.d, e, sh.d);
+        const float4 x = load4_nb<VW>(z + (i * sh.n + id) * sh.d, true, e, sh.d);  // branch-free: loads overlap
         v[0] += (double)x.x;
         v[1] += (double)x.y;
         v[2] += (double)x.z;

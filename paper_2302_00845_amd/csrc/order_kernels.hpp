@@ -162,7 +162,7 @@ __global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *
 #pragma unroll
         for (int k = 0; k < kGradPrefetch; ++k) {
             const int r = lane + 64 * k;
-            xn[k] = (r < in_dim) ? X[e * in_dim + r] : 0.f;
+            xn[k] = X[e * in_dim + (r < in_dim ? r : in_dim - 1)];  // clamped, not branched: the loads overlap
         }
     }
     for (; e < N; e += e_step) {
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(kGradWaves * 64) void softmax_pergrad(const float *
 #pragma unroll
                 for (int k = 0; k < kGradPrefetch; ++k) {
                     const int r = lane + 64 * k;
-                    xn[k] = (r < in_dim) ? X[(e + e_step) * in_dim + r] : 0.f;
+                    xn[k] = X[(e + e_step) * in_dim + (r < in_dim ? r : in_dim - 1)];
                 }
             }
         } else {
