@@ -269,11 +269,23 @@ __global__ __launch_bounds__(kDeltaWaves * 64) void train_step_delta(const float
     const int64_t id = perm ? (int64_t)perm[i * n + j] : j;
     const float *x = X + (i * n + id) * in_dim;
     for (int c = wave; c < classes; c += kDeltaWaves) {
+        // sixteen rows per lane at a time, every load issued before the first use
+        // (clamped indices instead of a ragged last batch: no branch between the loads)
         float part = 0.f;
-#pragma unroll 16
-        for (int r = lane; r <= in_dim; r += 64) {
-            const float xv = x[r < in_dim ? r : in_dim - 1];
-            part = fmaf(r < in_dim ? xv : 1.0f, W[r * classes + c], part);  // bias input 1
+        for (int r0 = lane; r0 <= in_dim; r0 += 64 * 16) {
+            float xv[16], wv[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int r = r0 + 64 * u;
+                const int rw = r <= in_dim ? r : in_dim;
+                xv[u] = x[rw < in_dim ? rw : in_dim - 1];
+                wv[u] = W[rw * classes + c];
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int r = r0 + 64 * u;
+                if (r <= in_dim) part = fmaf(r < in_dim ? xv[u] : 1.0f, wv[u], part);  // bias input 1
+            }
         }
         const float z = wave_sum(part);
         if (lane == 0) logit[c] = z;
