@@ -152,7 +152,7 @@ struct PrevBlock {
 };
 
 // `group` of `ngroups` workgroups share the tiles; the workgroup's result goes to `out`.
-template <int BB, int VW, int TE, bool APPLY>
+template <int BB, int VW, int TE, bool APPLY, bool NB>
 __device__ __forceinline__ void pass1_body(const RowMap &rm, const PrevBlock &prev, double *__restrict__ r_sum,
                                            double *__restrict__ out, int64_t ntiles, int group, int ngroups)
 {
@@ -204,11 +204,11 @@ __device__ __forceinline__ void pass1_body(const RowMap &rm, const PrevBlock &pr
         }
     }
 
-    // Short rows (TE = 64: one or two tiles per workgroup, the launch is bound by latency)
-    // load without branches; the streaming configuration keeps the plain loads.  Rows of
+    // NB (one block of short rows: one or two tiles per workgroup, the launch is bound by
+    // latency): loads without branches; the streaming uses keep the plain loads.  Rows of
     // the previous block that do not exist enter with sign 0, so they need no zeroing.
     auto tile_load = [&](const float *row, bool have, int64_t e) {
-        if constexpr (TE == 64) return load4_nb<VW>(row, have, e, d);
+        if constexpr (NB) return load4_nb<VW>(row, have, e, d);
         else return load4<VW>(have ? row : nullptr, e, d);
     };
 
@@ -355,8 +355,8 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, PrevBlock
                                                             double *__restrict__ partials,
                                                             int64_t ntiles)
 {
-    pass1_body<BB, VW, TE, APPLY>(rm, prev, r_sum, partials + (int64_t)blockIdx.x * PartLayout<BB>::PART, ntiles,
-                                  (int)blockIdx.x, (int)gridDim.x);
+    pass1_body<BB, VW, TE, APPLY, TE == 64>(rm, prev, r_sum, partials + (int64_t)blockIdx.x * PartLayout<BB>::PART,
+                                            ntiles, (int)blockIdx.x, (int)gridDim.x);
 }
 
 // The Gram matrices of many blocks in one launch (they depend on the rows only, not on
@@ -372,7 +372,7 @@ __global__ __launch_bounds__(kThreads) void gram_batched(const RowMap *__restric
     PrevBlock none;
     none.rm.nb = 0;
     none.eps = nullptr;
-    pass1_body<BB, VW, TE, false>(rm, none, r_sum,
+    pass1_body<BB, VW, TE, false, false>(rm, none, r_sum,
                                   partials + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * PartLayout<BB>::PART,
                                   ntiles, (int)blockIdx.x, (int)gridDim.x);
 }
@@ -533,9 +533,11 @@ __global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const doubl
     if (threadIdx.x >= 64) return;
     const int lane = threadIdx.x;
     // lane k keeps column k of the Gram matrix (= row k, it is symmetric) in registers
+    // (entries j >= lane are zeroed: lane k is updated at steps j < k only, and the walk
+    // then needs no lane test of its own)
     double col[BB];
 #pragma unroll
-    for (int j = 0; j < BB; ++j) col[j] = (lane < BB) ? G[lane][j] : 0.0;
+    for (int j = 0; j < BB; ++j) col[j] = (lane < BB && lane > j) ? G[lane][j] : 0.0;
     double t = (lane < nb) ? P[lane] : 0.0;
     // flattened pair of this lane -> (worker, pair) slot of the [m][n/2] arrays
     int64_t slot = 0;
@@ -552,13 +554,13 @@ __global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const doubl
     // Every lane applies the rule to its own t at every step; a wave-wide vote turns
     // lane j's answer into a scalar.  Lane k is updated at steps j < k only, so after
     // the loop its t is the resolved dot of pair k and the rule on it is pair k's sign.
+    // (Steps j >= nb of a short last block run too: they only touch lanes above j, which
+    // hold no pair.  Straight-line code, five instructions per step.)
 #pragma unroll
     for (int j = 0; j < BB; ++j) {
-        if (j < nb) {  // uniform
-            const bool plus_j = (__ballot(rule(t)) >> j) & 1ull;
-            const double cj = plus_j ? col[j] : -col[j];
-            if (lane > j) t += cj;
-        }
+        // +col[j] or -col[j]: the vote's bit j picks the sign bit to flip (a scalar)
+        const uint32_t flip = ((__ballot(rule(t)) >> j) & 1ull) ? 0u : 0x80000000u;
+        t += __hiloint2double(__double2hiint(col[j]) ^ (int)flip, __double2loint(col[j]));
     }
     const double my_t = t;
     const int my_eps = rule(t) ? 1 : -1;
