@@ -517,7 +517,7 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     if (ahead) {
         // enough workgroups to fill the chip, at least one tile each
         const int64_t ntiles = (d + plan.tile_elems - 1) / plan.tile_elems;
-        gram_groups = (int)std::max<int64_t>(1, std::min<int64_t>(ntiles, (8 * h->num_cu + batch - 1) / batch));
+        gram_groups = (int)std::max<int64_t>(1, std::min<int64_t>(ntiles, (4 * h->num_cu + batch - 1) / batch));
         rc = ensure(h, h->partials, h->partials_cap, batch * gram_groups * part_size(bb));
         if (rc) return rc;
         rc = ensure(h, h->gram_all, h->gram_all_cap, batch * part_size(bb));
