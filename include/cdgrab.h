@@ -49,9 +49,10 @@ typedef struct cdgrab_options {
     int32_t gram_mode;   /* dense input only.  1 = every block computes its Gram matrix in
                             its own dot/Gram launch; 2 = the Gram matrices of up to 512
                             blocks are computed ahead in one launch (they depend on the
-                            rows only) and a block then costs one dots + apply launch and
-                            the resolver; 0 = choose (2 for rows up to 16 384 elements when
-                            apply_mode is 0 as well)                                      */
+                            rows only) and a block then costs one launch (the previous
+                            block's resolver and apply, this block's dots); refused
+                            (EINVAL) for d > 131 072; 0 = choose (2 for rows up to 16 384
+                            elements when apply_mode is 0 as well)                        */
 } cdgrab_options;
 
 /* Event-timed durations of the last cdgrab_balance_epoch call (timing >= 1);

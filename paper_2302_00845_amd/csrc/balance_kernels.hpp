@@ -439,32 +439,33 @@ __global__ __launch_bounds__(kThreads) void reduce_partials(const double *__rest
 // keeps 64 doubles of the Gram matrix per lane in registers.
 template <int BB> constexpr int kResolveThreads = BB > 32 ? 512 : 1024;
 
-template <int BB, bool RANDOM, int SLICES>
-__global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const double *__restrict__ gram_src,
-                                                                     int64_t gram_stride,
-                                                                     const double *__restrict__ dot_src,
-                                                                     int dot_groups, int64_t dot_stride, int nb,
-                                                                     int64_t k0, int32_t i0, int32_t m, int64_t half_n,
-                                                                     int8_t *__restrict__ eps_blk,
-                                                                     int8_t *__restrict__ signs_out,
-                                                                     double *__restrict__ dots_out,
-                                                                     const float *__restrict__ uniforms)
+// The resolver's body, run by all NT threads of a workgroup (the walk by its first
+// wavefront).  write_out: store the signs (and resolved dots) to global memory; eps_lds
+// (LDS, BB entries, or null): the block's signs for the rest of the workgroup, valid after
+// the barrier this function ends with.
+template <int BB, bool RANDOM, int SLICES, int NT>
+__device__ __forceinline__ void resolve_body(const double *__restrict__ gram_src, int64_t gram_stride,
+                                             const double *__restrict__ dot_src, int dot_groups,
+                                             int64_t dot_stride, int nb, int64_t k0, int32_t i0, int32_t m,
+                                             int64_t half_n, bool write_out, int8_t *__restrict__ eps_blk,
+                                             int8_t *__restrict__ signs_out, double *__restrict__ dots_out,
+                                             const float *__restrict__ uniforms, int8_t *eps_lds)
 {
     // Gram tiles: sum of SLICES arrays gram_src[s * gram_stride + idx];
     // dots: sum of dot_groups arrays dot_src[g * dot_stride + k]; both in index order.
     using L = PartLayout<BB>;
-    constexpr int NT = kResolveThreads<BB>;
     constexpr int SUBS = (NT / BB < 16) ? NT / BB : 16;  // threads sharing one dot
     __shared__ double G[BB][BB + 1];
     __shared__ double P[BB];
     __shared__ double psub[BB][SUBS + 1];
-    // The dots' first sixteen groups per thread are requested before anything else and
+    // The dots' first DV groups per thread are requested before anything else and
     // consumed after the Gram tiles: indices beyond the last group re-read it and count
     // as zero, so that no branch separates the loads.
+    constexpr int DV = (256 / SUBS < 32) ? 256 / SUBS : 32;  // loads per thread in the first batch
     const int dk = (threadIdx.x / SUBS) % BB, dsub = threadIdx.x % SUBS;
-    double dv[16];
+    double dv[DV];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
+    for (int u = 0; u < DV; ++u) {
         const int g = dsub + u * SUBS;
         dv[u] = dot_src[(int64_t)(g < dot_groups ? g : dot_groups - 1) * dot_stride + dk];
     }
@@ -508,9 +509,9 @@ __global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const doubl
     if (threadIdx.x < BB * SUBS) {
         double sum = 0.0;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) sum += (dsub + u * SUBS < dot_groups) ? dv[u] : 0.0;
-        // (more than 16 * SUBS groups: the rest in further batches of sixteen loads)
-        for (int g0 = dsub + 16 * SUBS; g0 < dot_groups; g0 += 16 * SUBS) {
+        for (int u = 0; u < DV; ++u) sum += (dsub + u * SUBS < dot_groups) ? dv[u] : 0.0;
+        // (more than DV * SUBS groups: the rest in further batches of sixteen loads)
+        for (int g0 = dsub + DV * SUBS; g0 < dot_groups; g0 += 16 * SUBS) {
             double v[16];
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
@@ -530,45 +531,64 @@ __global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const doubl
         P[threadIdx.x] = sum;
     }
     __syncthreads();
-    if (threadIdx.x >= 64) return;
-    const int lane = threadIdx.x;
-    // lane k keeps column k of the Gram matrix (= row k, it is symmetric) in registers
-    // (entries j >= lane are zeroed: lane k is updated at steps j < k only, and the walk
-    // then needs no lane test of its own)
-    double col[BB];
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        // lane k keeps column k of the Gram matrix (= row k, it is symmetric) in registers
+        // (entries j >= lane are zeroed: lane k is updated at steps j < k only, and the walk
+        // then needs no lane test of its own)
+        double col[BB];
 #pragma unroll
-    for (int j = 0; j < BB; ++j) col[j] = (lane < BB && lane > j) ? G[lane][j] : 0.0;
-    double t = (lane < nb) ? P[lane] : 0.0;
-    // flattened pair of this lane -> (worker, pair) slot of the [m][n/2] arrays
-    int64_t slot = 0;
-    if (lane < nb) {
-        uint32_t q = (uint32_t)(i0 + lane);
-        uint32_t dk = q / (uint32_t)m;
-        slot = (int64_t)(q - dk * (uint32_t)m) * half_n + (k0 + dk);
-    }
-    // randomized rule (PairBalance's RandomizedBalance subroutine, Sec. 3.2): with
-    // c = z1 - z2 = -d, the first row gets +1 with probability p = (1 - <r,c>)/2 =
-    // (1 + t)/2, so the exported sign (of the second row) is -1 when u < p.
-    const float my_u = (RANDOM && lane < nb) ? uniforms[slot] : 0.f;
-    auto rule = [&](double tv) { return RANDOM ? !((double)my_u < 0.5 * (1.0 + tv)) : (tv <= 0.0); };
-    // Every lane applies the rule to its own t at every step; a wave-wide vote turns
-    // lane j's answer into a scalar.  Lane k is updated at steps j < k only, so after
-    // the loop its t is the resolved dot of pair k and the rule on it is pair k's sign.
-    // (Steps j >= nb of a short last block run too: they only touch lanes above j, which
-    // hold no pair.  Straight-line code, five instructions per step.)
+        for (int j = 0; j < BB; ++j) col[j] = (lane < BB && lane > j) ? G[lane][j] : 0.0;
+        double t = (lane < nb) ? P[lane] : 0.0;
+        // flattened pair of this lane -> (worker, pair) slot of the [m][n/2] arrays
+        int64_t slot = 0;
+        if (lane < nb) {
+            uint32_t q = (uint32_t)(i0 + lane);
+            uint32_t dq = q / (uint32_t)m;
+            slot = (int64_t)(q - dq * (uint32_t)m) * half_n + (k0 + dq);
+        }
+        // randomized rule (PairBalance's RandomizedBalance subroutine, Sec. 3.2): with
+        // c = z1 - z2 = -d, the first row gets +1 with probability p = (1 - <r,c>)/2 =
+        // (1 + t)/2, so the exported sign (of the second row) is -1 when u < p.
+        const float my_u = (RANDOM && lane < nb) ? uniforms[slot] : 0.f;
+        auto rule = [&](double tv) { return RANDOM ? !((double)my_u < 0.5 * (1.0 + tv)) : (tv <= 0.0); };
+        // Every lane applies the rule to its own t at every step; a wave-wide vote turns
+        // lane j's answer into a scalar.  Lane k is updated at steps j < k only, so after
+        // the loop its t is the resolved dot of pair k and the rule on it is pair k's sign.
+        // (Steps j >= nb of a short last block run too: they only touch lanes above j, which
+        // hold no pair.  Straight-line code, five instructions per step.)
 #pragma unroll
-    for (int j = 0; j < BB; ++j) {
-        // +col[j] or -col[j]: the vote's bit j picks the sign bit to flip (a scalar)
-        const uint32_t flip = ((__ballot(rule(t)) >> j) & 1ull) ? 0u : 0x80000000u;
-        t += __hiloint2double(__double2hiint(col[j]) ^ (int)flip, __double2loint(col[j]));
+        for (int j = 0; j < BB; ++j) {
+            // +col[j] or -col[j]: the vote's bit j picks the sign bit to flip (a scalar)
+            const uint32_t flip = ((__ballot(rule(t)) >> j) & 1ull) ? 0u : 0x80000000u;
+            t += __hiloint2double(__double2hiint(col[j]) ^ (int)flip, __double2loint(col[j]));
+        }
+        const double my_t = t;
+        const int my_eps = rule(t) ? 1 : -1;
+        if (eps_lds && lane < BB) eps_lds[lane] = (lane < nb) ? (int8_t)my_eps : (int8_t)0;
+        if (write_out && lane < nb) {
+            eps_blk[lane] = (int8_t)my_eps;
+            signs_out[slot] = (int8_t)my_eps;
+            if (dots_out) dots_out[slot] = my_t;
+        }
     }
-    const double my_t = t;
-    const int my_eps = rule(t) ? 1 : -1;
-    if (lane < nb) {
-        eps_blk[lane] = (int8_t)my_eps;
-        signs_out[slot] = (int8_t)my_eps;
-        if (dots_out) dots_out[slot] = my_t;
-    }
+    __syncthreads();
+}
+
+template <int BB, bool RANDOM, int SLICES>
+__global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const double *__restrict__ gram_src,
+                                                                     int64_t gram_stride,
+                                                                     const double *__restrict__ dot_src,
+                                                                     int dot_groups, int64_t dot_stride, int nb,
+                                                                     int64_t k0, int32_t i0, int32_t m, int64_t half_n,
+                                                                     int8_t *__restrict__ eps_blk,
+                                                                     int8_t *__restrict__ signs_out,
+                                                                     double *__restrict__ dots_out,
+                                                                     const float *__restrict__ uniforms)
+{
+    resolve_body<BB, RANDOM, SLICES, kResolveThreads<BB>>(gram_src, gram_stride, dot_src, dot_groups, dot_stride, nb,
+                                                          k0, i0, m, half_n, true, eps_blk, signs_out, dots_out,
+                                                          uniforms, nullptr);
 }
 
 // ---------------------------------------------------------------------------
@@ -656,61 +676,61 @@ __global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const i
 }
 
 // ---------------------------------------------------------------------------
-// Short rows with the Gram matrices computed ahead (gram_batched): what is left on the
-// chain of a block is  r += sum_k eps_k d_k  over the PREVIOUS block, and the dots
-// <r, d_k> of this block against the result.  Same thread layout as
-// pass2_apply_split: a workgroup owns 64 elements, group g of 16 threads takes the
-// pairs g*PER .. g*PER+PER-1 of either block.  DENSE: row addresses by arithmetic
-// (RowMap::dense_row) instead of through the offset table.  Each workgroup writes its share of the
-// BB dots to dot_partials[blockIdx.x][BB]; the resolver adds the workgroups in order.
-template <int BB, int VW, bool DENSE>
-__global__ __launch_bounds__(kThreads) void dots_apply_split(RowMap rm, PrevBlock prev,
-                                                             double *__restrict__ r_sum,
-                                                             double *__restrict__ dot_partials)
+// Short rows with the Gram matrices computed ahead (gram_batched): the chain of a block
+// in ONE launch.  What is left on the chain is the resolver of the PREVIOUS block,
+// r += sum_k eps_k d_k over it, and the dots <r, d_k> of this block against the result.
+// Every workgroup resolves the previous block for itself (its reduced Gram tiles and the
+// per-workgroup dots the previous launch wrote: the resolver's body on 256 threads,
+// redundantly in each of the d/64 workgroups -- a few tens of KB from the L2 and a walk of
+// Bb steps, cheaper than a launch boundary).  Then, with the thread layout of
+// pass2_apply_split (a workgroup owns 64 elements, group g of 16 threads takes the pairs
+// g*PER .. g*PER+PER-1 of either block), it applies the previous block and writes its share
+// of this block's Bb dots to dots_out_part[blockIdx.x][BB], which must not be the array
+// being read.  Workgroup 0 also stores the previous block's signs.  DENSE: row addresses by
+// arithmetic (RowMap::dense_row) instead of through the offset table.
+template <int BB, int VW, bool DENSE, bool RANDOM>
+__global__ __launch_bounds__(kThreads) void resolve_dots_apply_split(
+    RowMap rm, PrevBlock prev, const double *__restrict__ prev_gram, const double *__restrict__ dots_in_part,
+    double *__restrict__ dots_out_part, int dot_groups, double *__restrict__ r_sum, int8_t *__restrict__ eps_blk,
+    int8_t *__restrict__ signs_out, double *__restrict__ dots_out, const float *__restrict__ uniforms)
 {
     __shared__ double part[kSplitGroups][kSplitElems];
     __shared__ double rnew[kSplitElems];
+    __shared__ int8_t eps_s[kMaxBlockPairs];
     const int64_t d = rm.d;
     constexpr int QUADS = kThreads / kSplitGroups;  // 16 threads, four elements each
     const int quad = threadIdx.x % QUADS, grp = threadIdx.x / QUADS;
     const int64_t e = (int64_t)blockIdx.x * kSplitElems + quad * 4;
     const int64_t mine = (int64_t)blockIdx.x * kSplitElems + threadIdx.x;
-    // all loads of the workgroup are requested up front: the launch is latency-bound
+    // the rows of both blocks are requested before the resolver's inputs
     const double r_old = (threadIdx.x < kSplitElems) ? r_sum[mine] : 0.0;  // padded to a multiple of 128
     constexpr int PER = BB / kSplitGroups;
     float4 pa[PER], pb[PER], ca[PER], cb[PER];
-    double sg[PER];
-    // Offsets of missing pairs are zero, so every row pointer is valid: no branch stands
-    // between the offset loads and the row loads, and a missing pair of the previous block
-    // enters with sign 0 (a missing pair of this block yields a dot nobody reads).
-    const float *rp[PER][4];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
         const int j = grp * PER + q;
-        // (a pair beyond the block's or the epoch's end maps to the block's first pair: readable)
         const int jp = j < prev.rm.nb ? j : 0, jc = j < rm.nb ? j : 0;
-        rp[q][0] = DENSE ? prev.rm.dense_row(jp, 0) : prev.rm.row(j, 0);
-        rp[q][1] = DENSE ? prev.rm.dense_row(jp, 1) : prev.rm.row(j, 1);
-        rp[q][2] = DENSE ? rm.dense_row(jc, 0) : rm.row(j, 0);
-        rp[q][3] = DENSE ? rm.dense_row(jc, 1) : rm.row(j, 1);
+        pa[q] = load4_nb<VW>(DENSE ? prev.rm.dense_row(jp, 0) : prev.rm.row(j, 0), true, e, d);
+        pb[q] = load4_nb<VW>(DENSE ? prev.rm.dense_row(jp, 1) : prev.rm.row(j, 1), true, e, d);
+        ca[q] = load4_nb<VW>(DENSE ? rm.dense_row(jc, 0) : rm.row(j, 0), true, e, d);
+        cb[q] = load4_nb<VW>(DENSE ? rm.dense_row(jc, 1) : rm.row(j, 1), true, e, d);
     }
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-        const int j = grp * PER + q;
-        pa[q] = load4_nb<VW>(rp[q][0], true, e, d);
-        pb[q] = load4_nb<VW>(rp[q][1], true, e, d);
-        ca[q] = load4_nb<VW>(rp[q][2], true, e, d);
-        cb[q] = load4_nb<VW>(rp[q][3], true, e, d);
-        const double ej = (double)prev.eps[j];  // 64 entries, always readable
-        sg[q] = (j < prev.rm.nb) ? ej : 0.0;
+    if (prev.rm.nb > 0) {  // uniform
+        resolve_body<BB, RANDOM, 1, kThreads>(prev_gram, 0, dots_in_part, dot_groups, BB, prev.rm.nb, prev.rm.k0,
+                                              prev.rm.i0, prev.rm.m, prev.rm.n / 2, blockIdx.x == 0, eps_blk,
+                                              signs_out, dots_out, uniforms, eps_s);
+    } else {
+        if (threadIdx.x < BB) eps_s[threadIdx.x] = 0;
+        __syncthreads();
     }
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-        acc[0] = __builtin_fma(sg[q], (double)pb[q].x - (double)pa[q].x, acc[0]);
-        acc[1] = __builtin_fma(sg[q], (double)pb[q].y - (double)pa[q].y, acc[1]);
-        acc[2] = __builtin_fma(sg[q], (double)pb[q].z - (double)pa[q].z, acc[2]);
-        acc[3] = __builtin_fma(sg[q], (double)pb[q].w - (double)pa[q].w, acc[3]);
+        const double sg = (double)eps_s[grp * PER + q];  // 0 for a pair the previous block does not have
+        acc[0] = __builtin_fma(sg, (double)pb[q].x - (double)pa[q].x, acc[0]);
+        acc[1] = __builtin_fma(sg, (double)pb[q].y - (double)pa[q].y, acc[1]);
+        acc[2] = __builtin_fma(sg, (double)pb[q].z - (double)pa[q].z, acc[2]);
+        acc[3] = __builtin_fma(sg, (double)pb[q].w - (double)pa[q].w, acc[3]);
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) part[grp][quad * 4 + q] = acc[q];
@@ -731,10 +751,9 @@ __global__ __launch_bounds__(kThreads) void dots_apply_split(RowMap rm, PrevBloc
         p = __builtin_fma(r1, (double)cb[q].y - (double)ca[q].y, p);
         p = __builtin_fma(r2, (double)cb[q].z - (double)ca[q].z, p);
         p = __builtin_fma(r3, (double)cb[q].w - (double)ca[q].w, p);
-        // the 16 threads of a group are 16 consecutive lanes
 #pragma unroll
         for (int off = 1; off < QUADS; off <<= 1) p += __shfl_xor(p, off, 64);
-        if (quad == 0) dot_partials[(int64_t)blockIdx.x * BB + grp * PER + q] = p;
+        if (quad == 0) dots_out_part[(int64_t)blockIdx.x * BB + grp * PER + q] = p;
     }
 }
 

@@ -110,12 +110,14 @@ bool fuse_apply_by_default(int64_t d) { return d <= ((int64_t)1 << 21); }
 
 // Dense input with short rows: a block is bound by its chain of launches, so the Gram
 // matrices (which depend on the rows only) are taken off the chain: one launch computes
-// them for up to kGramBatch blocks, and a block then costs a dots + apply launch and the
-// resolver.  Measured on MI355X (m = 16, 64-pair blocks), time per block of the per-block
-// form -> this form: d = 256: 21.5 -> 10.4 us; 4096: 22.7 -> 13.6; 16 384: 25.9 -> 21.3;
-// 32 768: 35.7 -> 34.6; 65 536: 48.4 -> 61.0 (the rows are read three times instead of twice).
+// them for up to kGramBatch blocks, and a block then costs one launch (resolver of the
+// previous block, its apply, this block's dots).  Measured on MI355X (m = 16, 64-pair blocks), time per block of the per-block
+// form -> this form: d = 256: 22.0 -> 8.9 us; 4096: 23.3 -> 11.2; 7850: 26.1 -> 15.8;
+// 16 384: 26.3 -> 19.3; 32 768: 35.9 -> 44.0; 65 536: 48.6 -> 132 (the rows are read three
+// times instead of twice, and every workgroup repeats the previous block's resolver).
 constexpr int64_t kGramBatch = 512;
-constexpr int64_t kGramAheadMaxD = 16384;
+constexpr int64_t kGramAheadMaxD = 16384;     // chosen by default up to here
+constexpr int64_t kGramAheadLimitD = 131072;  // refused beyond (gram_mode 2)
 bool gram_ahead_by_default(int64_t d, int64_t blocks, bool streamed) {
     return !streamed && blocks >= 2 && d <= kGramAheadMaxD;
 }
@@ -251,34 +253,48 @@ void launch_resolve(cdgrab_handle *h, const RowMap &rm, int8_t *signs_out, doubl
     else launch(resolve_signs<BB, false, kReduceSlices>);
 }
 
-// Grams-ahead form of one block: dots + apply of the previous block, then the resolver
-// on the block's reduced Gram tiles and the per-workgroup dots.
+// Grams-ahead form of one block, one launch: every workgroup resolves the previous block
+// (its Gram tiles at prev_gram, its per-workgroup dots in dots_in), applies it and takes
+// this block's dots (into dots_out).  The first block of an epoch has prev.rm.nb == 0.
 template <int BB>
 int run_block_ahead(cdgrab_handle *h, const RowMap &rm, const PrevBlock &prev, const cdgrab_plan &plan,
-                    const double *gram, int8_t *signs_out, double *dots_out) {
+                    const double *prev_gram, const double *dots_in, double *dots_out, int8_t *signs_out,
+                    double *dots_export) {
     const unsigned groups = (unsigned)((rm.d + kSplitElems - 1) / kSplitElems);
     MARK(h, 2, kPass1);
     auto launch = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, dim3(groups), dim3(kThreads), 0, h->stream, rm, prev, h->r_sum, h->dot_partials);
+        hipLaunchKernelGGL(kernel, dim3(groups), dim3(kThreads), 0, h->stream, rm, prev, prev_gram, dots_in,
+                           dots_out, (int)groups, h->r_sum, h->eps_blk, signs_out, dots_export, h->uniforms);
+    };
+    auto by_width = [&](auto dense_tag, auto random_tag) {
+        constexpr bool DENSE = decltype(dense_tag)::value, RANDOM = decltype(random_tag)::value;
+        switch (plan.vector_width) {
+            case 4: launch(resolve_dots_apply_split<BB, 4, DENSE, RANDOM>); break;
+            case 2: launch(resolve_dots_apply_split<BB, 2, DENSE, RANDOM>); break;
+            default: launch(resolve_dots_apply_split<BB, 1, DENSE, RANDOM>); break;
+        }
     };
     if (rm.dense) {
-        switch (plan.vector_width) {
-            case 4: launch(dots_apply_split<BB, 4, true>); break;
-            case 2: launch(dots_apply_split<BB, 2, true>); break;
-            default: launch(dots_apply_split<BB, 1, true>); break;
-        }
+        if (h->uniforms) by_width(std::true_type{}, std::true_type{});
+        else by_width(std::true_type{}, std::false_type{});
     } else {
-        switch (plan.vector_width) {
-            case 4: launch(dots_apply_split<BB, 4, false>); break;
-            case 2: launch(dots_apply_split<BB, 2, false>); break;
-            default: launch(dots_apply_split<BB, 1, false>); break;
-        }
+        if (h->uniforms) by_width(std::false_type{}, std::true_type{});
+        else by_width(std::false_type{}, std::false_type{});
     }
+    HIP_TRY(h, hipGetLastError());
+    return CDGRAB_OK;
+}
+
+// The resolver alone, for the epoch's last block in the Grams-ahead form.
+template <int BB>
+int run_resolve_ahead(cdgrab_handle *h, const RowMap &rm, const double *gram, const double *dots_in,
+                      int8_t *signs_out, double *dots_export) {
+    const int groups = (int)((rm.d + kSplitElems - 1) / kSplitElems);
     MARK(h, 2, kResolve);
     auto resolve = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, dim3(1), dim3(kResolveThreads<BB>), 0, h->stream, gram, (int64_t)0,
-                           h->dot_partials, (int)groups, (int64_t)BB, rm.nb, rm.k0, rm.i0, rm.m, rm.n / 2,
-                           h->eps_blk, signs_out, dots_out, h->uniforms);
+        hipLaunchKernelGGL(kernel, dim3(1), dim3(kResolveThreads<BB>), 0, h->stream, gram, (int64_t)0, dots_in,
+                           groups, (int64_t)BB, rm.nb, rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out,
+                           dots_export, h->uniforms);
     };
     if (h->uniforms) resolve(resolve_signs<BB, true, 1>);
     else resolve(resolve_signs<BB, false, 1>);
@@ -286,9 +302,10 @@ int run_block_ahead(cdgrab_handle *h, const RowMap &rm, const PrevBlock &prev, c
     return CDGRAB_OK;
 }
 
-// Gram tiles of `count` blocks (row maps already in h->maps) into h->gram_all.
+// Gram tiles of `count` blocks (row maps already in h->maps) into gram_out[count][PART].
 template <int BB>
-int run_grams_ahead(cdgrab_handle *h, int64_t d, const cdgrab_plan &plan, int64_t count, int groups) {
+int run_grams_ahead(cdgrab_handle *h, int64_t d, const cdgrab_plan &plan, int64_t count, int groups,
+                    double *gram_out) {
     constexpr int part = PartLayout<BB>::PART;
     const dim3 grid((unsigned)groups, (unsigned)count), block(kThreads);
     MARK(h, 2, kPass1);
@@ -309,7 +326,7 @@ int run_grams_ahead(cdgrab_handle *h, int64_t d, const cdgrab_plan &plan, int64_
     }
     MARK(h, 2, kReduce);
     hipLaunchKernelGGL(reduce_batched, dim3((part + kThreads - 1) / kThreads, (unsigned)count), block, 0, h->stream,
-                       h->partials, h->gram_all, part, groups);
+                       h->partials, gram_out, part, groups);
     HIP_TRY(h, hipGetLastError());
     return CDGRAB_OK;
 }
@@ -511,7 +528,12 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     const bool fused = h->apply_mode == 2 || (h->apply_mode == 0 && fuse_apply_by_default(d));
     const int64_t staging_chunk = chunk_pairs * 2 * d;  // floats per staging chunk
     if (streamed) { rc = ensure(h, h->staging, h->staging_cap, (fused ? 2 : 1) * staging_chunk); if (rc) return rc; }
-    // Grams ahead (dense input): asked for, or chosen for short rows when the caller left both choices open
+    // Grams ahead (dense input): asked for, or chosen for short rows when the caller left both choices open.
+    // (Every one of the d/64 workgroups of a block's launch reads all d/64 x Bb partial dots of the
+    // previous block: quadratic in d, which is why the form is refused for long rows.)
+    if (h->gram_mode == 2 && !streamed && d > kGramAheadLimitD)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: gram_mode 2 is for rows up to %lld elements (d=%lld)",
+                    (long long)kGramAheadLimitD, (long long)d);
     const bool ahead = !streamed && plan.blocks >= 2 &&
                        (h->gram_mode == 2 || (h->gram_mode == 0 && h->apply_mode == 0 && plan.gram_ahead));
     const int64_t batch = std::min<int64_t>(plan.blocks, kGramBatch);
@@ -522,9 +544,9 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
         gram_groups = (int)std::max<int64_t>(1, std::min<int64_t>(ntiles, (4 * h->num_cu + batch - 1) / batch));
         rc = ensure(h, h->partials, h->partials_cap, batch * gram_groups * part_size(bb));
         if (rc) return rc;
-        rc = ensure(h, h->gram_all, h->gram_all_cap, batch * part_size(bb));
+        rc = ensure(h, h->gram_all, h->gram_all_cap, (batch + 1) * part_size(bb));
         if (rc) return rc;
-        rc = ensure(h, h->dot_partials, h->dot_partials_cap, (d + kSplitElems - 1) / kSplitElems * bb);
+        rc = ensure(h, h->dot_partials, h->dot_partials_cap, 2 * ((d + kSplitElems - 1) / kSplitElems * bb));
         if (rc) return rc;
         rc = ensure(h, h->maps, h->maps_cap, batch);
         if (rc) return rc;
@@ -573,27 +595,50 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     prev.rm.nb = 0;
     bool have_prev = false;
     if (ahead) {
-        // Gram matrices of up to kGramBatch blocks in one launch, then the chain of blocks
+        // Gram matrices of up to kGramBatch blocks in one launch, then the chain of blocks.
+        // Slot 0 of gram_all carries the last block of the previous batch over; the
+        // per-workgroup dots alternate between two arrays (a launch reads the previous
+        // block's while it writes its own).
+        const int64_t part = part_size(bb);
+        const int64_t dot_len = (d + kSplitElems - 1) / kSplitElems * bb;
+        int64_t blk = 0, prev_slot = 0;
         for (int64_t b0 = 0; b0 < plan.blocks; b0 += batch) {
             const int64_t count = std::min<int64_t>(batch, plan.blocks - b0);
             MARK(h, 1, kBalance);
+            if (b0 > 0)
+                HIP_TRY(h, hipMemcpyAsync(h->gram_all, h->gram_all + prev_slot * part, (size_t)part * sizeof(double),
+                                          hipMemcpyDeviceToDevice, h->stream));
             hipLaunchKernelGGL(fill_row_maps, dim3((unsigned)count), dim3(kMaxBlockPairs), 0, h->stream, h->maps,
                                grads, m, n, d, bb, b0 * bb, plan.pairs, center_off, center_row ? 1 : 0);
-            rc = (bb == 64)   ? run_grams_ahead<64>(h, d, plan, count, gram_groups)
-                 : (bb == 32) ? run_grams_ahead<32>(h, d, plan, count, gram_groups)
-                              : run_grams_ahead<16>(h, d, plan, count, gram_groups);
+            rc = (bb == 64)   ? run_grams_ahead<64>(h, d, plan, count, gram_groups, h->gram_all + part)
+                 : (bb == 32) ? run_grams_ahead<32>(h, d, plan, count, gram_groups, h->gram_all + part)
+                              : run_grams_ahead<16>(h, d, plan, count, gram_groups, h->gram_all + part);
             if (rc) return rc;
-            for (int64_t b = 0; b < count; ++b) {
+            for (int64_t b = 0; b < count; ++b, ++blk) {
                 const int64_t p0 = (b0 + b) * bb;
                 set_block(p0, std::min<int64_t>(bb, plan.pairs - p0), nullptr);
-                const double *gram = h->gram_all + b * part_size(bb);
-                rc = (bb == 64)   ? run_block_ahead<64>(h, rm, prev, plan, gram, signs_out, dots_out)
-                     : (bb == 32) ? run_block_ahead<32>(h, rm, prev, plan, gram, signs_out, dots_out)
-                                  : run_block_ahead<16>(h, rm, prev, plan, gram, signs_out, dots_out);
+                // block b of this batch sits in slot b + 1, its predecessor in slot b
+                const double *prev_gram = h->gram_all + b * part;
+                const double *dots_in = h->dot_partials + ((blk + 1) & 1) * dot_len;
+                double *dots_mine = h->dot_partials + (blk & 1) * dot_len;
+                rc = (bb == 64)   ? run_block_ahead<64>(h, rm, prev, plan, prev_gram, dots_in, dots_mine, signs_out, dots_out)
+                     : (bb == 32) ? run_block_ahead<32>(h, rm, prev, plan, prev_gram, dots_in, dots_mine, signs_out, dots_out)
+                                  : run_block_ahead<16>(h, rm, prev, plan, prev_gram, dots_in, dots_mine, signs_out, dots_out);
                 if (rc) return rc;
                 prev.rm = rm;
                 have_prev = true;
             }
+            prev_slot = count;
+        }
+        // the last block: the resolver alone (its apply follows below)
+        {
+            const double *gram = h->gram_all + prev_slot * part;
+            const double *dots_in = h->dot_partials + ((blk + 1) & 1) * dot_len;
+            MARK(h, 1, kBalance);
+            rc = (bb == 64)   ? run_resolve_ahead<64>(h, prev.rm, gram, dots_in, signs_out, dots_out)
+                 : (bb == 32) ? run_resolve_ahead<32>(h, prev.rm, gram, dots_in, signs_out, dots_out)
+                              : run_resolve_ahead<16>(h, prev.rm, gram, dots_in, signs_out, dots_out);
+            if (rc) return rc;
         }
     } else {
         const int64_t chunk = streamed ? chunk_pairs : plan.pairs;

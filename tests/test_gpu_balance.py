@@ -113,6 +113,14 @@ def test_grams_ahead_and_per_block_agree(lib, m, n, d, bb):
     check_epoch(z, run_epoch(lib, z, block_pairs=bb, gram_mode=1))
 
 
+def test_grams_ahead_is_refused_for_long_rows(lib):
+    h = lib.Handle(gram_mode=2)
+    z = torch.zeros((1, 4, 131072 + 4), dtype=torch.float32, device="cuda")
+    with pytest.raises(lib.CdgrabError) as ei:
+        lib.cdgrab_balance_epoch(h, 1, 4, z.shape[2], grads=z)
+    assert ei.value.code == -1
+
+
 def test_grams_ahead_over_several_batches(lib):
     """More blocks than one ahead-launch covers (512): the last block of a batch is the
     previous block of the next batch's first."""
