@@ -248,9 +248,9 @@ def main():
         pairs = N // 2
         avg_pairs = pairs / blocks
         if ahead:
-            # per block: its share of the batched Gram launch (rows once) and the dots + apply
+            # per block: its share of the batched Gram launch (rows once) and the resolve + apply + dots
             # launch (rows of this block and of the previous one, running sum read and written)
-            per_kernel = (("gram_batched+dots_apply", tp["pass1_ms"] + tp["pass2_ms"],
+            per_kernel = (("gram_batched+resolve_dots_apply", tp["pass1_ms"] + tp["pass2_ms"],
                            24.0 * avg_pairs * d + 16.0 * d),)
         elif not fused:
             # algorithmic bytes per launch: both rows of every pair in the block (fp32) plus the
