@@ -133,6 +133,30 @@ def test_grams_ahead_over_several_batches(lib):
     check_epoch(zi, a, expect_exact_signs=True)
 
 
+def _random_cases(count):
+    rng = np.random.default_rng(20230200845)
+    cases = []
+    for _ in range(count):
+        m = int(rng.integers(1, 12))
+        n = 2 * int(rng.integers(1, 40))
+        d = int(rng.choice([1, 2, 3, 17, 63, 64, 65, 127, 130, 255, 1000, 4097, 20000]))
+        bb = int(rng.choice([0, 16, 32, 64]))
+        apply_mode = int(rng.integers(0, 3))
+        gram_mode = int(rng.integers(0, 3))
+        cases.append((m, n, d, bb, apply_mode, gram_mode))
+    return cases
+
+
+@pytest.mark.parametrize("m,n,d,bb,apply_mode,gram_mode", _random_cases(32))
+def test_seeded_random_shapes_exact(lib, m, n, d, bb, apply_mode, gram_mode):
+    """Seeded draw of shapes and launch forms on exact-arithmetic inputs: whatever the block
+    size, apply form and Gram form, signs, order and running sum equal the oracle's bit for bit."""
+    zi = workloads.integer_rows(m * 1000 + n + d, m, n, d, 5)
+    perm = workloads.random_perms(d, m, n)
+    got = run_epoch(lib, zi, perm_in=perm, block_pairs=bb, apply_mode=apply_mode, gram_mode=gram_mode)
+    check_epoch(zi, got, perm, expect_exact_signs=True)
+
+
 def test_unaligned_base_pointer(lib):
     """A gradient array that starts 4 bytes into an allocation takes the scalar-load path."""
     m, n, d = 3, 10, 1001
