@@ -780,15 +780,16 @@ __global__ void fill_zero_f64(double *p, int64_t count) {
     for (; i < count; i += stride) p[i] = 0.0;
 }
 
-// Row maps of `count` consecutive blocks of a dense input [m][n][d], starting at
-// flattened pair first_pair: block b holds the pairs first_pair + b*bb .. (up to
-// total_pairs).  With center_off >= 0 the input is n single rows, each paired with
-// the row at element offset center_off (see RowMap).  One thread per (block, pair).
+// Row maps of `count` consecutive blocks starting at flattened pair first_pair: block b
+// holds the pairs first_pair + b*bb .. (up to total_pairs).  One thread per (block, pair).
 __global__ __launch_bounds__(kMaxBlockPairs) void fill_row_maps(RowMap *__restrict__ maps, const float *base,
                                                                 int64_t m, int64_t n, int64_t d, int bb,
                                                                 int64_t first_pair, int64_t total_pairs,
-                                                                int64_t center_off, int use_center)
+                                                                int64_t center_off, int layout)
 {
+    // layout 0: dense [m][n][d];  1: single rows paired with the row at center_off;
+    // 2: a staging chunk [q][2][d] that starts at first_pair (base = the chunk)
+    const int use_center = layout == 1;
     RowMap &rm = maps[blockIdx.x];
     const int j = threadIdx.x;
     const int64_t p0 = first_pair + (int64_t)blockIdx.x * bb;
@@ -802,7 +803,7 @@ __global__ __launch_bounds__(kMaxBlockPairs) void fill_row_maps(RowMap *__restri
         rm.i0 = (int32_t)(p0 - (p0 / m) * m);
         rm.m = (int32_t)m;
         rm.nb = nb;
-        rm.dense = use_center ? 0 : 1;
+        rm.dense = layout == 0 ? 1 : 0;
     }
     int64_t o0 = 0, o1 = 0;
     if (j < nb) {
@@ -810,6 +811,9 @@ __global__ __launch_bounds__(kMaxBlockPairs) void fill_row_maps(RowMap *__restri
         if (use_center) {
             o0 = p * d;
             o1 = center_off;
+        } else if (layout == 2) {
+            o0 = (p - first_pair) * 2 * d;
+            o1 = o0 + d;
         } else {
             const int64_t k = p / m, i = p - k * m;
             o0 = (i * n + 2 * k) * d;

@@ -534,9 +534,18 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     if (h->gram_mode == 2 && !streamed && d > kGramAheadLimitD)
         return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: gram_mode 2 is for rows up to %lld elements (d=%lld)",
                     (long long)kGramAheadLimitD, (long long)d);
-    const bool ahead = !streamed && plan.blocks >= 2 &&
-                       (h->gram_mode == 2 || (h->gram_mode == 0 && h->apply_mode == 0 && plan.gram_ahead));
-    const int64_t batch = std::min<int64_t>(plan.blocks, kGramBatch);
+    const bool ahead_dense = !streamed && plan.blocks >= 2 &&
+                             (h->gram_mode == 2 || (h->gram_mode == 0 && h->apply_mode == 0 && plan.gram_ahead));
+    // the same for short streamed rows when a staging chunk holds several whole blocks
+    const bool ahead_streamed = streamed && h->gram_mode != 1 && h->apply_mode == 0 && d <= kGramAheadMaxD &&
+                                plan.pairs > bb && chunk_pairs >= 2 * bb && chunk_pairs % bb == 0 &&
+                                chunk_pairs / bb <= kGramBatch;
+    const bool ahead = ahead_dense || ahead_streamed;
+    const int64_t batch = streamed ? chunk_pairs / bb : std::min<int64_t>(plan.blocks, kGramBatch);
+    if (ahead_streamed) {  // two chunks: the previous block's rows outlive the next chunk's fill
+        rc = ensure(h, h->staging, h->staging_cap, 2 * staging_chunk);
+        if (rc) return rc;
+    }
     int gram_groups = 1;
     if (ahead) {
         // enough workgroups to fill the chip, at least one tile each
@@ -589,6 +598,7 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
             rm.off[2 * j + 1] = rm.off[2 * j] + d;
         }
     };
+    if (streamed) rm.base = h->staging;  // (readable, see above)
     PrevBlock prev;
     prev.eps = h->eps_blk;
     prev.rm = rm;
@@ -601,22 +611,33 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
         // block's while it writes its own).
         const int64_t part = part_size(bb);
         const int64_t dot_len = (d + kSplitElems - 1) / kSplitElems * bb;
-        int64_t blk = 0, prev_slot = 0;
-        for (int64_t b0 = 0; b0 < plan.blocks; b0 += batch) {
+        int64_t blk = 0, prev_slot = 0, batch_index = 0;
+        for (int64_t b0 = 0; b0 < plan.blocks; b0 += batch, ++batch_index) {
             const int64_t count = std::min<int64_t>(batch, plan.blocks - b0);
+            const int64_t first = b0 * bb, cnt_pairs = std::min<int64_t>(count * bb, plan.pairs - first);
+            float *stage_buf = streamed ? h->staging + (batch_index & 1) * staging_chunk : nullptr;
+            if (streamed) {
+                MARK(h, 1, kGen);
+                int grc = gen(gen_ctx, first, cnt_pairs, stage_buf, h->stream);
+                if (grc != 0)
+                    return fail(h, CDGRAB_EGEN, "generator callback returned %d at pair %lld", grc,
+                                (long long)first);
+            }
             MARK(h, 1, kBalance);
             if (b0 > 0)
                 HIP_TRY(h, hipMemcpyAsync(h->gram_all, h->gram_all + prev_slot * part, (size_t)part * sizeof(double),
                                           hipMemcpyDeviceToDevice, h->stream));
             hipLaunchKernelGGL(fill_row_maps, dim3((unsigned)count), dim3(kMaxBlockPairs), 0, h->stream, h->maps,
-                               grads, m, n, d, bb, b0 * bb, plan.pairs, center_off, center_row ? 1 : 0);
+                               streamed ? stage_buf : grads, m, n, d, bb, first, plan.pairs, center_off,
+                               streamed ? 2 : (center_row ? 1 : 0));
             rc = (bb == 64)   ? run_grams_ahead<64>(h, d, plan, count, gram_groups, h->gram_all + part)
                  : (bb == 32) ? run_grams_ahead<32>(h, d, plan, count, gram_groups, h->gram_all + part)
                               : run_grams_ahead<16>(h, d, plan, count, gram_groups, h->gram_all + part);
             if (rc) return rc;
             for (int64_t b = 0; b < count; ++b, ++blk) {
                 const int64_t p0 = (b0 + b) * bb;
-                set_block(p0, std::min<int64_t>(bb, plan.pairs - p0), nullptr);
+                set_block(p0, std::min<int64_t>(bb, plan.pairs - p0),
+                          streamed ? stage_buf + (p0 - first) * 2 * d : nullptr);
                 // block b of this batch sits in slot b + 1, its predecessor in slot b
                 const double *prev_gram = h->gram_all + b * part;
                 const double *dots_in = h->dot_partials + ((blk + 1) & 1) * dot_len;
@@ -822,9 +843,18 @@ int cdgrab_train_epoch_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t i
     if (rc) return rc;
     TrainCtx ctx{h, m, n, in_dim, classes, (in_dim + 1) * classes, X, y, perm_in, W, velocity,
                  grads_out, loss_out, lr, momentum};
-    // a chunk is a whole number of step pairs: about one block's worth of pairs, at least one step pair
+    // a chunk is a whole number of step pairs: about one block's worth of pairs, at least one step pair;
+    // for short rows eight blocks' worth (or as many as make it whole blocks), so that the Gram
+    // matrices of a chunk are computed in one launch and a block costs a single one
     const int64_t step_pairs = std::max<int64_t>(1, 64 / m);
-    return balance_epoch_impl(h, m, n, ctx.d, nullptr, train_generate, &ctx, step_pairs * m, perm_in,
+    int64_t chunk = step_pairs * m;
+    if (ctx.d <= kGramAheadMaxD && h->gram_mode != 1 && h->apply_mode == 0) {
+        const int64_t bb = pick_block_pairs(m * (n / 2), ctx.d, h->block_pairs_opt);
+        int64_t k = 8;
+        if ((chunk * k) % bb != 0) k = bb;  // chunk * bb is a multiple of bb
+        if (chunk * k / bb <= kGramBatch && chunk * k * 2 * ctx.d * 4 * 2 <= ((int64_t)1 << 30)) chunk *= k;
+    }
+    return balance_epoch_impl(h, m, n, ctx.d, nullptr, train_generate, &ctx, chunk, perm_in,
                               signs_out, perm_out, nullptr, nullptr, nullptr);
 }
 
