@@ -46,7 +46,8 @@ typedef struct cdgrab_options {
                             apply launch after the block is resolved; 2 = inside the next
                             block's dot/Gram launch (one streaming launch per block, the
                             running sum read once per block); 0 = choose by row length  */
-    int32_t gram_mode;   /* dense input only.  1 = every block computes its Gram matrix in
+    int32_t gram_mode;   /* dense input (and the staged rows of cdgrab_train_epoch_softmax).
+                            1 = every block computes its Gram matrix in
                             its own dot/Gram launch; 2 = the Gram matrices of up to 512
                             blocks are computed ahead in one launch (they depend on the
                             rows only) and a block then costs one launch (the previous
