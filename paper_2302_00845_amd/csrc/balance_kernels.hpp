@@ -774,6 +774,14 @@ __global__ __launch_bounds__(kThreads) void stream_read_probe(const float4_t *__
 }
 
 // ---------------------------------------------------------------------------
+// Clears `count` 32-bit words.  The library clears its flags and scratch with fill
+// kernels rather than memset nodes, so that a caller may capture its stream in a graph.
+__global__ void fill_zero_b32(uint32_t *p, int64_t count) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) p[i] = 0u;
+}
+
 __global__ void fill_zero_f64(double *p, int64_t count) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;

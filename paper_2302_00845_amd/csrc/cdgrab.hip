@@ -753,7 +753,8 @@ int cdgrab_balance_epoch_stale_mean(cdgrab_handle *h, int64_t n, int64_t d, cons
     if (!stale_mean) {
         rc = ensure(h, h->zero_row, h->zero_row_cap, d);
         if (rc) return rc;
-        HIP_TRY(h, hipMemsetAsync(h->zero_row, 0, (size_t)d * sizeof(float), h->stream));
+        hipLaunchKernelGGL(fill_zero_b32, dim3((unsigned)std::min<int64_t>(4096, (d + 255) / 256)), dim3(256), 0,
+                           h->stream, reinterpret_cast<uint32_t *>(h->zero_row), d);
         stale_mean = h->zero_row;
     }
     if (!h->flag) { int64_t cap = 0; rc = ensure(h, h->flag, cap, (int64_t)1); if (rc) return rc; }
@@ -763,7 +764,7 @@ int cdgrab_balance_epoch_stale_mean(cdgrab_handle *h, int64_t n, int64_t d, cons
                             r64_out, nullptr, stale_mean);
     if (rc) return rc;
     hipLaunchKernelGGL(negate_signs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, h->stream, signs_out, n);
-    HIP_TRY(h, hipMemsetAsync(h->flag, 0, sizeof(int32_t), h->stream));
+    hipLaunchKernelGGL(fill_zero_b32, dim3(1), dim3(64), 0, h->stream, reinterpret_cast<uint32_t *>(h->flag), (int64_t)1);
     hipLaunchKernelGGL(reorder_from_signs, dim3(1), dim3(kScanThreads), 0, h->stream, signs_out, perm_in,
                        perm_out, n, h->flag);
     if (mean_out)
@@ -895,7 +896,7 @@ int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,
     if (!signs || !perm_out) return fail(h, CDGRAB_EINVAL, "cdgrab_reorder: null pointer");
     HIP_TRY(h, hipSetDevice(h->device));
     if (!h->flag) { int64_t cap = 0; int rc = ensure(h, h->flag, cap, (int64_t)1); if (rc) return rc; }
-    HIP_TRY(h, hipMemsetAsync(h->flag, 0, sizeof(int32_t), h->stream));
+    hipLaunchKernelGGL(fill_zero_b32, dim3(1), dim3(64), 0, h->stream, reinterpret_cast<uint32_t *>(h->flag), (int64_t)1);
     hipLaunchKernelGGL(reorder_from_signs, dim3((unsigned)m), dim3(kScanThreads), 0, h->stream, signs,
                        perm_in, perm_out, n, h->flag);
     HIP_TRY(h, hipGetLastError());
