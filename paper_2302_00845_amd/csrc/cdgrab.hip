@@ -481,30 +481,58 @@ int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
     return CDGRAB_OK;
 }
 
-// One epoch.  With a generator, `chunk_pairs` flattened pairs are staged per callback
-// (0 = one block) and balanced block by block out of the staging buffer.
-// With `center_row` (dense input, m == 1) every row j is paired with that one row
-// instead of with its neighbour: "pair" j is (row j, center_row), n pairs in all, and
-// the permutation is left to the caller (perm_out may be null).
-static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *grads,
-                              cdgrab_gen_fn gen, void *gen_ctx, int64_t chunk_pairs,
-                              const int32_t *perm_in, int8_t *signs_out, int32_t *perm_out,
-                              float *r_out, double *r64_out, double *dots_out,
-                              const float *center_row = nullptr) {
-    if (!h) return CDGRAB_EINVAL;
+// Dispatch on the block size, which is a template parameter of the launch helpers.
+#define BY_BLOCK_PAIRS(bb, call64, call32, call16) ((bb) == 64 ? (call64) : (bb) == 32 ? (call32) : (call16))
+
+namespace {
+
+// One epoch's state: what the caller gave, the plan, the launch form chosen, and the
+// row map of the current and of the previous block.
+struct Epoch {
+    cdgrab_handle *h;
+    int64_t m, n, d;
+    const float *grads;        // dense input, or null: rows come from gen
+    cdgrab_gen_fn gen;
+    void *gen_ctx;
+    int64_t chunk_pairs;       // flattened pairs staged per generator call
+    const float *center_row;   // dense, m == 1: every row is paired with this one
+    int8_t *signs_out;
+    double *dots_out;
+
+    bool streamed = false;
+    cdgrab_plan plan{};
+    int bb = 0;
+    bool fused = false;        // apply inside the next block's dot/Gram launch
+    bool ahead = false;        // Gram matrices of a batch of blocks ahead, one launch per block
+    int64_t batch = 0;         // blocks per ahead-launch (a staging chunk's blocks when streaming)
+    int gram_groups = 1;       // workgroups per block of the ahead-launch
+    int64_t staging_chunk = 0; // floats per staging chunk
+    int64_t center_off = 0;    // element offset of center_row from grads
+
+    RowMap rm;
+    PrevBlock prev;
+    bool have_prev = false;
+
+    int prepare();
+    void set_block(int64_t p0, int64_t nb, const float *stage_base);
+    int generate(int64_t first, int64_t count, float *stage_buf);
+    int chain_ahead();
+    int chain_blocks();
+    int apply_last();
+};
+
+// Validation, plan, choice of the launch form, workspace.
+int Epoch::prepare() {
     if (m < 1 || n < 2 || (n & 1) || d < 1)
         return fail(h, CDGRAB_EINVAL,
                     "cdgrab_balance_epoch: need m>=1, even n>=2, d>=1 (got m=%lld n=%lld d=%lld)",
                     (long long)m, (long long)n, (long long)d);
     if ((grads == nullptr) == (gen == nullptr))
         return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: give exactly one of grads and gen");
-    if (!signs_out || (!perm_out && !center_row))
-        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: signs_out and perm_out are required");
     if (n > INT32_MAX) return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: n exceeds int32 range");
     HIP_TRY(h, hipSetDevice(h->device));
 
-    const bool streamed = grads == nullptr;
-    cdgrab_plan plan;
+    streamed = grads == nullptr;
     int64_t align = 16;
     if (!streamed) {
         uintptr_t a = reinterpret_cast<uintptr_t>(grads);
@@ -514,21 +542,12 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     }
     int rc = plan_epoch(m, n, d, h->block_pairs_opt, streamed, align, h->num_cu, h->pass1_groups_opt, &plan);
     if (rc != CDGRAB_OK) return fail(h, rc, "cdgrab_balance_epoch: sizes overflow or are invalid");
-    const int bb = plan.block_pairs;
-
-    // workspace
-    int64_t fixed_cap = 0;
-    rc = ensure(h, h->r_sum, h->r_cap, round_up(d, kPadE));
-    if (rc) return rc;
-    rc = ensure(h, h->partials, h->partials_cap, (int64_t)plan.pass1_groups * part_size(bb));
-    if (rc) return rc;
-    if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)kReduceSlices * PartLayout<64>::PART); if (rc) return rc; }
-    if (!h->eps_blk) { fixed_cap = 0; rc = ensure(h, h->eps_blk, fixed_cap, (int64_t)64); if (rc) return rc; }
+    bb = plan.block_pairs;
     if (chunk_pairs <= 0) chunk_pairs = bb;
-    const bool fused = h->apply_mode == 2 || (h->apply_mode == 0 && fuse_apply_by_default(d));
-    const int64_t staging_chunk = chunk_pairs * 2 * d;  // floats per staging chunk
-    if (streamed) { rc = ensure(h, h->staging, h->staging_cap, (fused ? 2 : 1) * staging_chunk); if (rc) return rc; }
-    // Grams ahead (dense input): asked for, or chosen for short rows when the caller left both choices open.
+    staging_chunk = chunk_pairs * 2 * d;
+    fused = h->apply_mode == 2 || (h->apply_mode == 0 && fuse_apply_by_default(d));
+
+    // Grams ahead: asked for, or chosen for short rows when the caller left both choices open.
     // (Every one of the d/64 workgroups of a block's launch reads all d/64 x Bb partial dots of the
     // previous block: quadratic in d, which is why the form is refused for long rows.)
     if (h->gram_mode == 2 && !streamed && d > kGramAheadLimitD)
@@ -540,13 +559,22 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     const bool ahead_streamed = streamed && h->gram_mode != 1 && h->apply_mode == 0 && d <= kGramAheadMaxD &&
                                 plan.pairs > bb && chunk_pairs >= 2 * bb && chunk_pairs % bb == 0 &&
                                 chunk_pairs / bb <= kGramBatch;
-    const bool ahead = ahead_dense || ahead_streamed;
-    const int64_t batch = streamed ? chunk_pairs / bb : std::min<int64_t>(plan.blocks, kGramBatch);
-    if (ahead_streamed) {  // two chunks: the previous block's rows outlive the next chunk's fill
-        rc = ensure(h, h->staging, h->staging_cap, 2 * staging_chunk);
+    ahead = ahead_dense || ahead_streamed;
+    batch = streamed ? chunk_pairs / bb : std::min<int64_t>(plan.blocks, kGramBatch);
+
+    // workspace
+    int64_t fixed_cap = 0;
+    rc = ensure(h, h->r_sum, h->r_cap, round_up(d, kPadE));
+    if (rc) return rc;
+    rc = ensure(h, h->partials, h->partials_cap, (int64_t)plan.pass1_groups * part_size(bb));
+    if (rc) return rc;
+    if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)kReduceSlices * PartLayout<64>::PART); if (rc) return rc; }
+    if (!h->eps_blk) { fixed_cap = 0; rc = ensure(h, h->eps_blk, fixed_cap, (int64_t)64); if (rc) return rc; }
+    if (streamed) {
+        // two chunks when a launch reads the previous block's rows as well: they must outlive the next fill
+        rc = ensure(h, h->staging, h->staging_cap, ((fused || ahead) ? 2 : 1) * staging_chunk);
         if (rc) return rc;
     }
-    int gram_groups = 1;
     if (ahead) {
         // enough workgroups to fill the chip, at least one tile each
         const int64_t ntiles = (d + plan.tile_elems - 1) / plan.tile_elems;
@@ -561,159 +589,179 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
         if (rc) return rc;
     }
 
+    center_off = center_row ? (int64_t)((reinterpret_cast<intptr_t>(center_row) - reinterpret_cast<intptr_t>(grads)) /
+                                        (intptr_t)sizeof(float))
+                            : 0;
+    rm.d = d; rm.m = (int32_t)m; rm.n = n; rm.dense = (!streamed && !center_row) ? 1 : 0;
+    rm.k0 = 0; rm.i0 = 0; rm.nb = 0;
+    // (a copy of this map stands in for "no previous block": its rows must be readable)
+    rm.base = streamed ? h->staging : grads;
+    for (int64_t &o : rm.off) o = 0;
+    prev.eps = h->eps_blk;
+    prev.rm = rm;
+    have_prev = false;
+    return CDGRAB_OK;
+}
+
+// Row offsets of the block of flattened pairs p0 .. p0+nb-1 (dense input), or of a
+// staging chunk's rows [2 q], [2 q + 1] starting at stage_base.
+void Epoch::set_block(int64_t p0, int64_t nb, const float *stage_base) {
+    rm.k0 = p0 / m;
+    rm.i0 = (int32_t)(p0 - rm.k0 * m);
+    rm.nb = (int32_t)nb;
+    if (stage_base) rm.base = stage_base;
+    for (int j = 0; j < rm.nb; ++j) {
+        if (stage_base) {
+            rm.off[2 * j] = (int64_t)(2 * j) * d;
+        } else if (center_row) {
+            rm.off[2 * j] = (p0 + j) * d;
+            rm.off[2 * j + 1] = center_off;
+            continue;
+        } else {
+            const int64_t p = p0 + j, k = p / m, i = p - k * m;
+            rm.off[2 * j] = (i * n + 2 * k) * d;
+        }
+        rm.off[2 * j + 1] = rm.off[2 * j] + d;
+    }
+}
+
+int Epoch::generate(int64_t first, int64_t count, float *stage_buf) {
+    MARK(h, 1, kGen);
+    const int grc = gen(gen_ctx, first, count, stage_buf, h->stream);
+    if (grc != 0)
+        return fail(h, CDGRAB_EGEN, "generator callback returned %d at pair %lld", grc, (long long)first);
+    return CDGRAB_OK;
+}
+
+// Gram matrices of a batch of blocks in one launch, then one launch per block.  Slot 0 of
+// gram_all carries the last block of the previous batch over; the per-workgroup dots
+// alternate between two arrays (a launch reads the previous block's while it writes its own).
+int Epoch::chain_ahead() {
+    const int64_t part = part_size(bb);
+    const int64_t dot_len = (d + kSplitElems - 1) / kSplitElems * bb;
+    int64_t blk = 0, prev_slot = 0, batch_index = 0;
+    int rc = CDGRAB_OK;
+    for (int64_t b0 = 0; b0 < plan.blocks; b0 += batch, ++batch_index) {
+        const int64_t count = std::min<int64_t>(batch, plan.blocks - b0);
+        const int64_t first = b0 * bb, cnt_pairs = std::min<int64_t>(count * bb, plan.pairs - first);
+        float *stage_buf = streamed ? h->staging + (batch_index & 1) * staging_chunk : nullptr;
+        if (streamed && (rc = generate(first, cnt_pairs, stage_buf))) return rc;
+        MARK(h, 1, kBalance);
+        if (b0 > 0)
+            HIP_TRY(h, hipMemcpyAsync(h->gram_all, h->gram_all + prev_slot * part, (size_t)part * sizeof(double),
+                                      hipMemcpyDeviceToDevice, h->stream));
+        hipLaunchKernelGGL(fill_row_maps, dim3((unsigned)count), dim3(kMaxBlockPairs), 0, h->stream, h->maps,
+                           streamed ? stage_buf : grads, m, n, d, bb, first, plan.pairs, center_off,
+                           streamed ? 2 : (center_row ? 1 : 0));
+        double *gram_out = h->gram_all + part;
+        rc = BY_BLOCK_PAIRS(bb, run_grams_ahead<64>(h, d, plan, count, gram_groups, gram_out),
+                            run_grams_ahead<32>(h, d, plan, count, gram_groups, gram_out),
+                            run_grams_ahead<16>(h, d, plan, count, gram_groups, gram_out));
+        if (rc) return rc;
+        for (int64_t b = 0; b < count; ++b, ++blk) {
+            const int64_t p0 = (b0 + b) * bb;
+            set_block(p0, std::min<int64_t>(bb, plan.pairs - p0), streamed ? stage_buf + (p0 - first) * 2 * d : nullptr);
+            // block b of this batch sits in slot b + 1, its predecessor in slot b
+            const double *prev_gram = h->gram_all + b * part;
+            const double *dots_in = h->dot_partials + ((blk + 1) & 1) * dot_len;
+            double *dots_mine = h->dot_partials + (blk & 1) * dot_len;
+            rc = BY_BLOCK_PAIRS(bb,
+                                run_block_ahead<64>(h, rm, prev, plan, prev_gram, dots_in, dots_mine, signs_out, dots_out),
+                                run_block_ahead<32>(h, rm, prev, plan, prev_gram, dots_in, dots_mine, signs_out, dots_out),
+                                run_block_ahead<16>(h, rm, prev, plan, prev_gram, dots_in, dots_mine, signs_out, dots_out));
+            if (rc) return rc;
+            prev.rm = rm;
+            have_prev = true;
+        }
+        prev_slot = count;
+    }
+    // the last block: the resolver alone (its apply follows)
+    const double *gram = h->gram_all + prev_slot * part;
+    const double *dots_in = h->dot_partials + ((blk + 1) & 1) * dot_len;
+    MARK(h, 1, kBalance);
+    return BY_BLOCK_PAIRS(bb, run_resolve_ahead<64>(h, prev.rm, gram, dots_in, signs_out, dots_out),
+                          run_resolve_ahead<32>(h, prev.rm, gram, dots_in, signs_out, dots_out),
+                          run_resolve_ahead<16>(h, prev.rm, gram, dots_in, signs_out, dots_out));
+}
+
+// Block by block: dot/Gram launch (with the previous block's apply inside it when
+// fused), reduction, resolver, and the apply launch when it is not fused.
+int Epoch::chain_blocks() {
+    const int64_t chunk = streamed ? chunk_pairs : plan.pairs;
+    int64_t chunk_index = 0;
+    int rc = CDGRAB_OK;
+    for (int64_t first = 0; first < plan.pairs; first += chunk, ++chunk_index) {
+        const int64_t cnt = std::min<int64_t>(chunk, plan.pairs - first);
+        // with the fused pass the previous block's rows must outlive this chunk's staging
+        float *stage_buf = h->staging + ((fused && (chunk_index & 1)) ? staging_chunk : 0);
+        if (streamed && (rc = generate(first, cnt, stage_buf))) return rc;
+        for (int64_t p0 = first; p0 < first + cnt; p0 += bb) {
+            set_block(p0, std::min<int64_t>(bb, first + cnt - p0), streamed ? stage_buf + (p0 - first) * 2 * d : nullptr);
+            MARK(h, 1, kBalance);
+            const PrevBlock *pp = (fused && have_prev) ? &prev : nullptr;
+            rc = BY_BLOCK_PAIRS(bb, run_block_vw<64>(h, rm, pp, !fused, plan, signs_out, dots_out),
+                                run_block_vw<32>(h, rm, pp, !fused, plan, signs_out, dots_out),
+                                run_block_vw<16>(h, rm, pp, !fused, plan, signs_out, dots_out));
+            if (rc) return rc;
+            prev.rm = rm;
+            have_prev = true;
+        }
+    }
+    return CDGRAB_OK;
+}
+
+// The epoch's last block has no successor to apply it.
+int Epoch::apply_last() {
+    if (!(fused || ahead) || !have_prev) return CDGRAB_OK;
+    MARK(h, 1, kBalance);
+    return BY_BLOCK_PAIRS(bb, apply_block_vw<64>(h, prev.rm, plan), apply_block_vw<32>(h, prev.rm, plan),
+                          apply_block_vw<16>(h, prev.rm, plan));
+}
+
+}  // namespace
+
+// One epoch.  With a generator, `chunk_pairs` flattened pairs are staged per callback
+// (0 = one block) and balanced block by block out of the staging buffer.
+// With `center_row` (dense input, m == 1) every row j is paired with that one row
+// instead of with its neighbour: "pair" j is (row j, center_row), n pairs in all, and
+// the permutation is left to the caller (perm_out may be null).
+static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *grads,
+                              cdgrab_gen_fn gen, void *gen_ctx, int64_t chunk_pairs,
+                              const int32_t *perm_in, int8_t *signs_out, int32_t *perm_out,
+                              float *r_out, double *r64_out, double *dots_out,
+                              const float *center_row = nullptr) {
+    if (!h) return CDGRAB_EINVAL;
+    if (!signs_out || (!perm_out && !center_row))
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: signs_out and perm_out are required");
+    Epoch ep{h, m, n, d, grads, gen, gen_ctx, chunk_pairs, center_row, signs_out, dots_out};
+    int rc = ep.prepare();
+    if (rc) return rc;
+
     h->marks.clear();
     h->events_used = 0;
     h->have_timing = false;
-
     hipLaunchKernelGGL(fill_zero_f64, dim3(std::min<int64_t>(4096, (h->r_cap + 255) / 256)), dim3(256), 0,
                        h->stream, h->r_sum, h->r_cap);
+    rc = ep.ahead ? ep.chain_ahead() : ep.chain_blocks();
+    if (rc) return rc;
+    rc = ep.apply_last();
+    if (rc) return rc;
 
-    RowMap rm;
-    rm.d = d; rm.m = (int32_t)m; rm.n = n; rm.dense = (!streamed && !center_row) ? 1 : 0;
-    rm.k0 = 0; rm.i0 = 0; rm.nb = 0;  // (a copy of this map stands in for "no previous block": its rows must be readable)
-    rm.base = grads;
-    for (int64_t &o : rm.off) o = 0;
-    const int64_t center_off =
-        center_row ? (int64_t)((reinterpret_cast<intptr_t>(center_row) - reinterpret_cast<intptr_t>(grads)) /
-                               (intptr_t)sizeof(float))
-                   : 0;
-    // row offsets of the block of flattened pairs p0 .. p0+nb-1 (dense input), or of a
-    // staging chunk's rows [2 q], [2 q + 1]
-    auto set_block = [&](int64_t p0, int64_t nb, const float *stage_base) {
-        rm.k0 = p0 / m;
-        rm.i0 = (int32_t)(p0 - rm.k0 * m);
-        rm.nb = (int32_t)nb;
-        if (stage_base) rm.base = stage_base;
-        for (int j = 0; j < rm.nb; ++j) {
-            if (stage_base) {
-                rm.off[2 * j] = (int64_t)(2 * j) * d;
-            } else if (center_row) {
-                rm.off[2 * j] = (p0 + j) * d;
-                rm.off[2 * j + 1] = center_off;
-                continue;
-            } else {
-                const int64_t p = p0 + j, k = p / m, i = p - k * m;
-                rm.off[2 * j] = (i * n + 2 * k) * d;
-            }
-            rm.off[2 * j + 1] = rm.off[2 * j] + d;
-        }
-    };
-    if (streamed) rm.base = h->staging;  // (readable, see above)
-    PrevBlock prev;
-    prev.eps = h->eps_blk;
-    prev.rm = rm;
-    prev.rm.nb = 0;
-    bool have_prev = false;
-    if (ahead) {
-        // Gram matrices of up to kGramBatch blocks in one launch, then the chain of blocks.
-        // Slot 0 of gram_all carries the last block of the previous batch over; the
-        // per-workgroup dots alternate between two arrays (a launch reads the previous
-        // block's while it writes its own).
-        const int64_t part = part_size(bb);
-        const int64_t dot_len = (d + kSplitElems - 1) / kSplitElems * bb;
-        int64_t blk = 0, prev_slot = 0, batch_index = 0;
-        for (int64_t b0 = 0; b0 < plan.blocks; b0 += batch, ++batch_index) {
-            const int64_t count = std::min<int64_t>(batch, plan.blocks - b0);
-            const int64_t first = b0 * bb, cnt_pairs = std::min<int64_t>(count * bb, plan.pairs - first);
-            float *stage_buf = streamed ? h->staging + (batch_index & 1) * staging_chunk : nullptr;
-            if (streamed) {
-                MARK(h, 1, kGen);
-                int grc = gen(gen_ctx, first, cnt_pairs, stage_buf, h->stream);
-                if (grc != 0)
-                    return fail(h, CDGRAB_EGEN, "generator callback returned %d at pair %lld", grc,
-                                (long long)first);
-            }
-            MARK(h, 1, kBalance);
-            if (b0 > 0)
-                HIP_TRY(h, hipMemcpyAsync(h->gram_all, h->gram_all + prev_slot * part, (size_t)part * sizeof(double),
-                                          hipMemcpyDeviceToDevice, h->stream));
-            hipLaunchKernelGGL(fill_row_maps, dim3((unsigned)count), dim3(kMaxBlockPairs), 0, h->stream, h->maps,
-                               streamed ? stage_buf : grads, m, n, d, bb, first, plan.pairs, center_off,
-                               streamed ? 2 : (center_row ? 1 : 0));
-            rc = (bb == 64)   ? run_grams_ahead<64>(h, d, plan, count, gram_groups, h->gram_all + part)
-                 : (bb == 32) ? run_grams_ahead<32>(h, d, plan, count, gram_groups, h->gram_all + part)
-                              : run_grams_ahead<16>(h, d, plan, count, gram_groups, h->gram_all + part);
-            if (rc) return rc;
-            for (int64_t b = 0; b < count; ++b, ++blk) {
-                const int64_t p0 = (b0 + b) * bb;
-                set_block(p0, std::min<int64_t>(bb, plan.pairs - p0),
-                          streamed ? stage_buf + (p0 - first) * 2 * d : nullptr);
-                // block b of this batch sits in slot b + 1, its predecessor in slot b
-                const double *prev_gram = h->gram_all + b * part;
-                const double *dots_in = h->dot_partials + ((blk + 1) & 1) * dot_len;
-                double *dots_mine = h->dot_partials + (blk & 1) * dot_len;
-                rc = (bb == 64)   ? run_block_ahead<64>(h, rm, prev, plan, prev_gram, dots_in, dots_mine, signs_out, dots_out)
-                     : (bb == 32) ? run_block_ahead<32>(h, rm, prev, plan, prev_gram, dots_in, dots_mine, signs_out, dots_out)
-                                  : run_block_ahead<16>(h, rm, prev, plan, prev_gram, dots_in, dots_mine, signs_out, dots_out);
-                if (rc) return rc;
-                prev.rm = rm;
-                have_prev = true;
-            }
-            prev_slot = count;
-        }
-        // the last block: the resolver alone (its apply follows below)
-        {
-            const double *gram = h->gram_all + prev_slot * part;
-            const double *dots_in = h->dot_partials + ((blk + 1) & 1) * dot_len;
-            MARK(h, 1, kBalance);
-            rc = (bb == 64)   ? run_resolve_ahead<64>(h, prev.rm, gram, dots_in, signs_out, dots_out)
-                 : (bb == 32) ? run_resolve_ahead<32>(h, prev.rm, gram, dots_in, signs_out, dots_out)
-                              : run_resolve_ahead<16>(h, prev.rm, gram, dots_in, signs_out, dots_out);
-            if (rc) return rc;
-        }
-    } else {
-        const int64_t chunk = streamed ? chunk_pairs : plan.pairs;
-        int64_t chunk_index = 0;
-        for (int64_t first = 0; first < plan.pairs; first += chunk, ++chunk_index) {
-            const int64_t cnt = std::min<int64_t>(chunk, plan.pairs - first);
-            // with the fused pass the previous block's rows must outlive this chunk's staging
-            float *stage_buf = h->staging + ((fused && (chunk_index & 1)) ? staging_chunk : 0);
-            if (streamed) {
-                MARK(h, 1, kGen);
-                int grc = gen(gen_ctx, first, cnt, stage_buf, h->stream);
-                if (grc != 0)
-                    return fail(h, CDGRAB_EGEN, "generator callback returned %d at pair %lld", grc,
-                                (long long)first);
-            }
-            for (int64_t p0 = first; p0 < first + cnt; p0 += bb) {
-                set_block(p0, std::min<int64_t>(bb, first + cnt - p0),
-                          streamed ? stage_buf + (p0 - first) * 2 * d : nullptr);
-                MARK(h, 1, kBalance);
-                const PrevBlock *pp = (fused && have_prev) ? &prev : nullptr;
-                rc = (bb == 64)   ? run_block_vw<64>(h, rm, pp, !fused, plan, signs_out, dots_out)
-                     : (bb == 32) ? run_block_vw<32>(h, rm, pp, !fused, plan, signs_out, dots_out)
-                                  : run_block_vw<16>(h, rm, pp, !fused, plan, signs_out, dots_out);
-                if (rc) return rc;
-                prev.rm = rm;
-                have_prev = true;
-            }
-        }
-    }
-    if ((fused || ahead) && have_prev) {  // the last block has no successor to apply it
-        MARK(h, 1, kBalance);
-        rc = (bb == 64)   ? apply_block_vw<64>(h, prev.rm, plan)
-             : (bb == 32) ? apply_block_vw<32>(h, prev.rm, plan)
-                          : apply_block_vw<16>(h, prev.rm, plan);
-        if (rc) return rc;
-    }
     MARK(h, 1, kFinish);
-    {
-        int64_t work = m * (n / 2);
-        if (!center_row)
-            hipLaunchKernelGGL(build_pair_permutations, dim3((unsigned)((work + 255) / 256)), dim3(256), 0,
-                               h->stream, signs_out, perm_in, perm_out, m, n);
-        if (r_out || r64_out)
-            hipLaunchKernelGGL(export_running_sum, dim3((unsigned)std::min<int64_t>(8192, (d + 255) / 256)),
-                               dim3(256), 0, h->stream, h->r_sum, d, r_out, r64_out);
-    }
+    if (!center_row)
+        hipLaunchKernelGGL(build_pair_permutations, dim3((unsigned)((m * (n / 2) + 255) / 256)), dim3(256), 0,
+                           h->stream, signs_out, perm_in, perm_out, m, n);
+    if (r_out || r64_out)
+        hipLaunchKernelGGL(export_running_sum, dim3((unsigned)std::min<int64_t>(8192, (d + 255) / 256)), dim3(256),
+                           0, h->stream, h->r_sum, d, r_out, r64_out);
     MARK(h, 1, -1);
     HIP_TRY(h, hipGetLastError());
+    const int64_t cp = ep.chunk_pairs, bb = ep.bb;
     h->last = cdgrab_timing{};
-    h->last.blocks = streamed ? ((plan.pairs / chunk_pairs) * ((chunk_pairs + bb - 1) / bb) +
-                                 ((plan.pairs % chunk_pairs) + bb - 1) / bb)
-                              : plan.blocks;
-    h->last.block_pairs = bb;
-    h->last.pass1_groups = plan.pass1_groups;
+    h->last.blocks = ep.streamed ? ((ep.plan.pairs / cp) * ((cp + bb - 1) / bb) + ((ep.plan.pairs % cp) + bb - 1) / bb)
+                                 : ep.plan.blocks;
+    h->last.block_pairs = (int32_t)bb;
+    h->last.pass1_groups = ep.plan.pass1_groups;
     h->have_timing = h->timing >= 1;
     return CDGRAB_OK;
 }
