@@ -195,6 +195,27 @@ def test_deterministic_and_group_count_invariant_on_exact_input(lib):
         assert np.array_equal(c[k], e[k]), k                     # exact input: grid does not matter
 
 
+def test_own_stream_and_handle_reuse_across_shapes(lib):
+    """One handle on a stream of its own (default priority), reused for epochs of different
+    shapes and forms (the workspace grows and shrinks its use), with work of another
+    handle on the default stream in between: every epoch equals the oracle's."""
+    stream = torch.cuda.Stream()
+    h = lib.Handle(stream=stream)
+    h0 = lib.Handle()
+    for seed, (m, n, d) in enumerate([(4, 32, 700), (2, 8, 50000), (8, 64, 64), (1, 2, 1), (3, 20, 9001)]):
+        zi = workloads.integer_rows(100 + seed, m, n, d, 5)
+        zt = torch.from_numpy(zi).cuda()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            out = lib.cdgrab_balance_epoch(h, m, n, d, grads=zt, want_r64=True, want_dots=True)
+        other = lib.cdgrab_balance_epoch(h0, m, n, d, grads=zt, want_r64=True)    # default stream, concurrently
+        stream.synchronize()
+        torch.cuda.synchronize()
+        got = {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
+        check_epoch(zi, got, expect_exact_signs=True)
+        assert torch.equal(other["signs"], out["signs"]) and torch.equal(other["r64"], out["r64"])
+
+
 def test_argument_errors(lib):
     h = lib.Handle()
     z = torch.zeros((2, 3, 4), dtype=torch.float32, device="cuda")
