@@ -13,7 +13,11 @@
  *     workspace (running sum, partial results, staging block).
  *   - Work is enqueued on the handle's HIP stream; a call returns once the work
  *     is enqueued unless stated otherwise.  The caller synchronises the stream
- *     before reading outputs.  Calls on one handle must not overlap.
+ *     before reading outputs.  Calls on one handle must not overlap.  The first
+ *     call with a given shape allocates workspace (and may synchronise the stream
+ *     to free a smaller one); later calls of cdgrab_pergrad and the balancing
+ *     entry points with dense input enqueue kernels and device-to-device copies
+ *     only, so they may be captured in a HIP graph.
  *   - Return value: CDGRAB_OK (0) or a negative error code.  After an error the
  *     contents of the outputs are undefined; cdgrab_last_error() gives a text.
  *   - Sizes are int64_t counts of elements, never bytes.
