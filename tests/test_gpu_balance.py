@@ -147,10 +147,15 @@ def _random_cases(count):
     return cases
 
 
-@pytest.mark.parametrize("m,n,d,bb,apply_mode,gram_mode", _random_cases(32))
+_WIDE_CASES = [(300, 4, 50, 0, 0, 0), (300, 4, 50, 32, 2, 1), (97, 6, 300, 16, 1, 1), (1, 600, 33, 0, 0, 0),
+               (64, 2, 1000, 64, 0, 2), (1000, 2, 7, 0, 0, 0)]
+
+
+@pytest.mark.parametrize("m,n,d,bb,apply_mode,gram_mode", _random_cases(32) + _WIDE_CASES)
 def test_seeded_random_shapes_exact(lib, m, n, d, bb, apply_mode, gram_mode):
-    """Seeded draw of shapes and launch forms on exact-arithmetic inputs: whatever the block
-    size, apply form and Gram form, signs, order and running sum equal the oracle's bit for bit."""
+    """Seeded draw of shapes and launch forms on exact-arithmetic inputs (plus a few with many
+    workers, where a block spans several steps, or a single one): whatever the block size, apply
+    form and Gram form, signs, order and running sum equal the oracle's bit for bit."""
     zi = workloads.integer_rows(m * 1000 + n + d, m, n, d, 5)
     perm = workloads.random_perms(d, m, n)
     got = run_epoch(lib, zi, perm_in=perm, block_pairs=bb, apply_mode=apply_mode, gram_mode=gram_mode)
