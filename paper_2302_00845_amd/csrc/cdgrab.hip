@@ -623,6 +623,10 @@ void Epoch::set_block(int64_t p0, int64_t nb, const float *stage_base) {
         }
         rm.off[2 * j + 1] = rm.off[2 * j] + d;
     }
+    // The kernels read the table without a branch, also for pairs the block does not have:
+    // those entries point at the block's first row, which is always readable (an entry left
+    // over from an earlier, fuller block could point past the end of a staging chunk).
+    for (int j = rm.nb; j < kMaxBlockPairs; ++j) rm.off[2 * j] = rm.off[2 * j + 1] = 0;
 }
 
 int Epoch::generate(int64_t first, int64_t count, float *stage_buf) {

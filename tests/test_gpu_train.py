@@ -27,6 +27,9 @@ def problem(seed, m, n, in_dim, classes, scale=10.0):
 @pytest.mark.parametrize("m,n,in_dim,classes,momentum", [
     (4, 16, 12, 3, 0.0), (4, 16, 12, 3, 0.9), (16, 12, 40, 10, 0.9), (3, 10, 7, 5, 0.5),
     (40, 6, 9, 4, 0.9), (1, 8, 5, 2, 0.0), (32, 4, 784, 10, 0.9), (80, 4, 6, 3, 0.9), (40, 4, 5, 250, 0.9),
+    # rows too long for the Gram-ahead form, 80 pairs per staging chunk: a full 64-pair block, then a
+    # 16-pair one whose row table still holds 48 entries of the full block
+    (80, 4, 2100, 8, 0.9),
 ])
 def test_epoch_matches_oracle(lib, m, n, in_dim, classes, momentum):
     X, y, W0 = problem(m + n, m, n, in_dim, classes)
