@@ -971,26 +971,30 @@ int cdgrab_herding_bound(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
     // enough (segment, element) threads to fill the chip, at least one step per segment
     const int64_t quads = (d + 3) / 4;
     int64_t want_threads = (int64_t)h->num_cu * 2048;
-    int64_t segs = std::max<int64_t>(1, std::min<int64_t>(n, (want_threads + quads - 1) / quads));
+    // a workgroup serves one segment: blockIdx.y (at most 65 535 of them)
+    int64_t segs = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(n, 65535), (want_threads + quads - 1) / quads));
     sh.seg_len = (n + segs - 1) / segs;
     sh.segments = (n + sh.seg_len - 1) / sh.seg_len;
     int rc = ensure(h, h->herd_ws, h->herd_cap, 2 * sh.segments * d + d);
     if (rc) return rc;
     double *segsum = h->herd_ws, *start = segsum + sh.segments * d, *zbar = start + sh.segments * d;
-    const int64_t threads = sh.segments * quads;
-    const unsigned grid = (unsigned)((threads + 255) / 256);
+    const dim3 grid((unsigned)((quads + 255) / 256), (unsigned)sh.segments);
     unsigned long long *bits = reinterpret_cast<unsigned long long *>(bound_out);
+    // the segment's example ids go through LDS when they fit (48 KB)
+    const size_t ids_bytes = (size_t)(sh.seg_len * m) * sizeof(int32_t);
+    const int lds_ids = (perm && ids_bytes <= 48 * 1024) ? 1 : 0;
+    const size_t lds = lds_ids ? ids_bytes : 0;
     // widest load every row start allows
     const uintptr_t zb = reinterpret_cast<uintptr_t>(z);
     const int vw = (d % 4 == 0 && zb % 16 == 0) ? 4 : (d % 2 == 0 && zb % 8 == 0) ? 2 : 1;
     hipLaunchKernelGGL(herding_clear, dim3(1), dim3(1), 0, h->stream, bits);
     auto launch = [&](auto vw_tag) {
         constexpr int VW = decltype(vw_tag)::value;
-        hipLaunchKernelGGL((herding_segment_sums<VW>), dim3(grid), dim3(256), 0, h->stream, z, perm, sh, segsum);
+        hipLaunchKernelGGL((herding_segment_sums<VW>), grid, dim3(256), lds, h->stream, z, perm, sh, lds_ids, segsum);
         hipLaunchKernelGGL(herding_segment_offsets, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, h->stream,
                            segsum, sh, zbar, start);
-        hipLaunchKernelGGL((herding_prefix_max<VW>), dim3(grid), dim3(256), 0, h->stream, z, perm, sh, zbar, start,
-                           bits);
+        hipLaunchKernelGGL((herding_prefix_max<VW>), grid, dim3(256), lds, h->stream, z, perm, sh, lds_ids, zbar,
+                           start, bits);
     };
     if (vw == 4) launch(std::integral_constant<int, 4>{});
     else if (vw == 2) launch(std::integral_constant<int, 2>{});

@@ -21,14 +21,16 @@ struct HerdingShape {
 };
 
 // Sum over the workers of elements e .. e+3 of step j's vectors.  VW = widest
-// aligned load every row start allows (as in the balancing kernels).
+// aligned load every row start allows (as in the balancing kernels).  ids: the m
+// example ids of the step (LDS), or null: read perm (or take j) per worker.
 template <int VW>
 __device__ __forceinline__ void herding_step_sum(const float *__restrict__ z, const int32_t *__restrict__ perm,
-                                                 const HerdingShape &sh, int64_t j, int64_t e, double v[4]) {
+                                                 const int32_t *ids, const HerdingShape &sh, int64_t j, int64_t e,
+                                                 double v[4]) {
     v[0] = v[1] = v[2] = v[3] = 0.0;
 #pragma unroll 8
     for (int64_t i = 0; i < sh.m; ++i) {
-        const int64_t id = perm ? (int64_t)perm[i * sh.n + j] : j;
+        const int64_t id = ids ? (int64_t)ids[i] : (perm ? (int64_t)perm[i * sh.n + j] : j);
         const float4 x = load4_nb<VW>(z + (i * sh.n + id) * sh.d, true, e, sh.d);  // branch-free: loads overlap
         v[0] += (double)x.x;
         v[1] += (double)x.y;
@@ -37,25 +39,43 @@ __device__ __forceinline__ void herding_step_sum(const float *__restrict__ z, co
     }
 }
 
+// A workgroup serves one segment (blockIdx.y).  With lds_ids it first copies the
+// segment's example ids perm[i][j0 .. j1) into LDS as ids[j - j0][i], so that the row
+// loads of a step do not wait for a lookup of their own.
+__device__ __forceinline__ const int32_t *herding_stage_ids(const int32_t *__restrict__ perm, const HerdingShape &sh,
+                                                            int64_t j0, int64_t j1, int lds_ids, int32_t *ids_lds) {
+    if (!lds_ids) return nullptr;
+    const int64_t count = (j1 - j0) * sh.m;
+    for (int64_t t = threadIdx.x; t < count; t += blockDim.x) {
+        const int64_t jj = t / sh.m, i = t - jj * sh.m;
+        ids_lds[t] = perm[i * sh.n + j0 + jj];
+    }
+    __syncthreads();
+    return ids_lds;
+}
+
 __device__ __forceinline__ int64_t herding_quads(const HerdingShape &sh) { return (sh.d + 3) / 4; }
 
 // Pass A: segsum[s][e] = sum over the segment's steps and all workers.  One thread
-// per (segment, four consecutive elements).
+// per (segment = blockIdx.y, four consecutive elements).
 template <int VW>
 __global__ __launch_bounds__(256) void herding_segment_sums(const float *__restrict__ z,
                                                             const int32_t *__restrict__ perm, HerdingShape sh,
-                                                            double *__restrict__ segsum)
+                                                            int lds_ids, double *__restrict__ segsum)
 {
+    extern __shared__ int32_t ids_lds[];
     const int64_t quads = herding_quads(sh);
-    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (g >= sh.segments * quads) return;
-    const int64_t s = g / quads, e = (g - s * quads) * 4;
+    const int64_t s = blockIdx.y;
     const int64_t j0 = s * sh.seg_len;
     const int64_t j1 = (j0 + sh.seg_len < sh.n) ? j0 + sh.seg_len : sh.n;
+    const int32_t *ids = herding_stage_ids(perm, sh, j0, j1, lds_ids, ids_lds);
+    const int64_t qd = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (qd >= quads) return;
+    const int64_t e = qd * 4;
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     for (int64_t j = j0; j < j1; ++j) {
         double v[4];
-        herding_step_sum<VW>(z, perm, sh, j, e, v);
+        herding_step_sum<VW>(z, perm, ids ? ids + (j - j0) * sh.m : nullptr, sh, j, e, v);
 #pragma unroll
         for (int q = 0; q < 4; ++q) acc[q] += v[q];
     }
@@ -93,18 +113,21 @@ __global__ __launch_bounds__(256) void herding_segment_offsets(const double *__r
 template <int VW>
 __global__ __launch_bounds__(256) void herding_prefix_max(const float *__restrict__ z,
                                                           const int32_t *__restrict__ perm, HerdingShape sh,
-                                                          const double *__restrict__ zbar,
+                                                          int lds_ids, const double *__restrict__ zbar,
                                                           const double *__restrict__ start,
                                                           unsigned long long *__restrict__ bound_bits)
 {
     __shared__ double wave_max[4];
+    extern __shared__ int32_t ids_lds[];
     const int64_t quads = herding_quads(sh);
-    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t s = blockIdx.y;
+    const int64_t j0 = s * sh.seg_len;
+    const int64_t j1 = (j0 + sh.seg_len < sh.n) ? j0 + sh.seg_len : sh.n;
+    const int32_t *ids = herding_stage_ids(perm, sh, j0, j1, lds_ids, ids_lds);
+    const int64_t qd = (int64_t)blockIdx.x * 256 + threadIdx.x;
     double mx = 0.0;
-    if (g < sh.segments * quads) {
-        const int64_t s = g / quads, e = (g - s * quads) * 4;
-        const int64_t j0 = s * sh.seg_len;
-        const int64_t j1 = (j0 + sh.seg_len < sh.n) ? j0 + sh.seg_len : sh.n;
+    if (qd < quads) {
+        const int64_t e = qd * 4;
         double centre[4], acc[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -114,7 +137,7 @@ __global__ __launch_bounds__(256) void herding_prefix_max(const float *__restric
         }
         for (int64_t j = j0; j < j1; ++j) {
             double v[4];
-            herding_step_sum<VW>(z, perm, sh, j, e, v);
+            herding_step_sum<VW>(z, perm, ids ? ids + (j - j0) * sh.m : nullptr, sh, j, e, v);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 acc[q] += v[q] - centre[q];
