@@ -159,7 +159,7 @@ def main():
 
     import paper_2302_00845_amd as pkg
     import workloads
-    from workloads import synth
+    from workloads import hbm_probe, synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -280,7 +280,7 @@ def main():
                     "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"]}
         hp.close()
     # practical ceiling: a plain streaming read of a buffer the size of one block's rows
-    read_ceiling = h.measure_read_bandwidth(int(min(max(8.0 * bb * d, 1 << 28), 3 << 30)))
+    read_ceiling = hbm_probe.read_bandwidth(int(min(max(8.0 * bb * d, 1 << 28), 3 << 30)))
     if roofline is not None:
         roofline["plain_read_GBs"] = read_ceiling
         roofline["frac_of_plain_read"] = roofline["achieved"] / read_ceiling

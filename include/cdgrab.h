@@ -75,19 +75,22 @@ typedef struct cdgrab_timing {
     int32_t pass1_groups;/* workgroups used by the dot/Gram pass               */
 } cdgrab_timing;
 
-/* How one epoch is cut into blocks (pure host arithmetic; needs no GPU). */
+/* How one epoch is cut into blocks and launched (pure host arithmetic; needs no GPU). */
 typedef struct cdgrab_plan {
     int64_t pairs;           /* m*n/2 flattened pair differences                      */
     int64_t blocks;          /* ceil(pairs / block_pairs)                             */
     int32_t block_pairs;     /* Bb                                                    */
     int32_t vector_width;    /* fp32 elements per global load: 4, 2 or 1              */
     int32_t tile_elems;      /* elements of d per LDS tile of the dot/Gram pass        */
-    int32_t fused_apply;     /* 1: apply fused into the next block's launch (apply_mode 0) */
+    int32_t fused_apply;     /* 1: apply fused into the next block's dot/Gram launch (0 when
+                                gram_ahead is 1: that form applies inside its own launch)  */
     int32_t pass1_groups;    /* workgroups of the dot/Gram pass                       */
     int32_t pass2_groups;    /* workgroups of the apply pass                          */
-    int32_t gram_ahead;      /* 1: Gram matrices computed ahead (gram_mode 0, dense input) */
+    int32_t gram_ahead;      /* 1: Gram matrices of many blocks computed ahead in one launch */
     int32_t reserved;
-    int64_t workspace_bytes; /* running sum + partials (+ staging when streaming)     */
+    int64_t workspace_bytes; /* everything the handle allocates for this epoch: running sum,
+                                partials, slice sums, block signs, the buffers of the
+                                Grams-ahead form when gram_ahead is 1, and staging          */
     int64_t staging_bytes;   /* staging blocks [Bb][2][d] fp32 (two when fused), 0 for dense input */
     double bytes_per_example;/* algorithmic HBM bytes per example: each row twice, plus the
                                 double running sum per block: 8d + 12 d / Bb (read twice,
@@ -115,10 +118,12 @@ int cdgrab_destroy(cdgrab_handle *h);
  * next call on it).  With h == NULL: the text of the last failed cdgrab_create. */
 const char *cdgrab_last_error(const cdgrab_handle *h);
 
-/* Blocking plan for an epoch of m workers x n rows x d parameters.  `streamed`
- * non-zero means rows come from a generator.  block_pairs 0 = automatic.
- * `base_align` is the byte alignment of the gradient base pointer (16 if unknown
- * allocations come from hipMalloc).  Host only.  Errors: EINVAL. */
+/* The plan a handle with default options (apply_mode 0, gram_mode 0, pass1_groups 0)
+ * follows on a 256-CU device for an epoch of m workers x n rows x d parameters;
+ * a handle on another device, or with those options set, may choose differently.
+ * `streamed` non-zero means rows come from a generator, one block per callback.
+ * block_pairs 0 = automatic.  `base_align` is the byte alignment of the gradient base
+ * pointer (16 for hipMalloc'ed memory).  Host only.  Errors: EINVAL. */
 int cdgrab_plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs,
                       int32_t streamed, int64_t base_align, cdgrab_plan *plan /*host*/);
 
@@ -156,7 +161,8 @@ int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
  * staging block owned by the handle.  Exactly one of the two must be given.
  *   perm_in   [m][n] int32 dev or NULL : example id at each visiting position
  *   signs_out [m][n/2] int8 dev        : eps per (worker, pair)
- *   perm_out  [m][n] int32 dev         : next epoch's order
+ *   perm_out  [m][n] int32 dev         : next epoch's order; must not overlap perm_in
+ *                                        (to carry an order over, alternate two buffers)
  *   r_out     [d] fp32 dev or NULL     : final running sum, rounded from double
  *   r64_out   [d] fp64 dev or NULL     : final running sum in double
  *   dots_out  [m][n/2] fp64 dev or NULL: t seen when each pair was decided
@@ -164,12 +170,31 @@ int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes,
  * (fp32 inputs); sums over d are taken in a fixed order, so results are
  * reproducible run to run.
  * Errors: EINVAL (m<1, n<2, n odd, d<1, null required pointer, both or neither of
- * grads / gen), ENOMEM, EHIP, EGEN. */
+ * grads / gen, perm_out overlapping perm_in), ENOMEM, EHIP, EGEN. */
 int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                          const float *grads, cdgrab_gen_fn gen, void *gen_ctx,
                          const int32_t *perm_in, int8_t *signs_out,
                          int32_t *perm_out, float *r_out, double *r64_out,
                          double *dots_out);
+
+/* cdgrab_balance_epoch for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same epoch
+ * on dense input, with the workspace (running sum, per-workgroup partials, slice sums,
+ * block signs) in a static device array of about 3.9 MB that each GPU the library runs
+ * on holds until the process ends.  It calls no hipMalloc / hipFree and records no timing
+ * events.  Rows of at most CDGRAB_STATIC_MAX_D elements; longer rows are refused (EINVAL).
+ * It runs the per-block launch form with at most 128 workgroups in the dot/Gram pass, so
+ * sums over d may be taken in another order than cdgrab_balance_epoch's (same result on
+ * exactly representable input, otherwise equal to double rounding).
+ * Arguments and outputs as cdgrab_balance_epoch with grads given (no generator).
+ * All calls on one GPU share that GPU's array, whatever their handle: calls that overlap
+ * in time on one GPU (two streams, two threads) race.  A call clears what it needs cleared.
+ * Errors: EINVAL (as cdgrab_balance_epoch; grads NULL; d > CDGRAB_STATIC_MAX_D), EHIP. */
+#define CDGRAB_STATIC_MAX_D 131072
+int cdgrab_balance_epoch_static(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
+                                const float *grads, const int32_t *perm_in, int8_t *signs_out,
+                                int32_t *perm_out, float *r_out, double *r64_out,
+                                double *dots_out);
 
 /* The epoch of cdgrab_balance_epoch with the randomized sign rule of the analysis
  * (PairBalance with its RandomizedBalance subroutine, Sec. 3.2; the paper's
@@ -193,8 +218,10 @@ int cdgrab_balance_epoch_randomized(cdgrab_handle *h, int64_t m, int64_t n, int6
  *   grads [n][d] fp32 dev in visiting order, stale_mean [d] fp32 dev or NULL (zero),
  *   perm_in [n] int32 dev or NULL, signs_out [n] int8 dev (s_j), perm_out [n] int32 dev,
  *   mean_out [d] fp32 dev or NULL: mean of this epoch's vectors (next epoch's stale
- *   mean; must not alias stale_mean), r64_out [d] fp64 dev or NULL: final running sum.
- * Same arithmetic as cdgrab_balance_epoch.  Errors: EINVAL, ENOMEM, EHIP. */
+ *   mean; must not overlap stale_mean), r64_out [d] fp64 dev or NULL: final running sum.
+ *   perm_out must not overlap perm_in.
+ * Same arithmetic as cdgrab_balance_epoch.  Errors: EINVAL (sizes, null, overlapping
+ * buffers), ENOMEM, EHIP. */
 int cdgrab_balance_epoch_stale_mean(cdgrab_handle *h, int64_t n, int64_t d, const float *grads,
                                     const float *stale_mean, const int32_t *perm_in,
                                     int8_t *signs_out, int32_t *perm_out, float *mean_out,
@@ -222,8 +249,10 @@ int cdgrab_balance_epoch_independent(cdgrab_handle *h, int64_t m, int64_t n, int
  *   grads_out [m][n][(in_dim+1)*classes] fp32 dev or NULL: the gradient rows in
  *     visiting order (for verification; the epoch itself keeps only a few steps' rows),
  *   loss_out [m][n] fp32 dev or NULL: loss of each example when it was visited.
+ *   perm_out must not overlap perm_in.
  * fp32 model arithmetic, double balancing arithmetic.
- * Errors: EINVAL (sizes, n odd, null, momentum without velocity), ENOMEM, EHIP. */
+ * Errors: EINVAL (sizes, n odd, null, momentum without velocity, overlapping orders),
+ * ENOMEM, EHIP. */
 int cdgrab_train_epoch_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t in_dim,
                                int64_t classes, const float *X, const int32_t *y,
                                const int32_t *perm_in, float *W, float *velocity, float lr,
@@ -250,9 +279,10 @@ int cdgrab_train_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t in_dim,
  * Signs", Sec. 2.1), one independent problem per worker:
  *   perm_out[i] = concat(L_pos, reverse(L_neg)), L_pos / L_neg the entries of
  *   perm_in[i] (identity if NULL) whose sign is +1 / -1, in visiting order.
- *   signs [m][n] int8 dev, perm_in [m][n] int32 dev or NULL, perm_out [m][n] int32 dev.
+ *   signs [m][n] int8 dev, perm_in [m][n] int32 dev or NULL, perm_out [m][n] int32 dev
+ *   (must not overlap perm_in).
  * This call synchronises the stream to report a sign that is not +1 or -1.
- * Errors: EINVAL (m<1, n<1, null pointer, bad sign value), EHIP. */
+ * Errors: EINVAL (m<1, n<1, null pointer, bad sign value, overlapping orders), EHIP. */
 int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,
                    const int32_t *perm_in, int32_t *perm_out);
 
@@ -265,12 +295,6 @@ int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,
  * Sums in double.  Errors: EINVAL (sizes, null), ENOMEM, EHIP. */
 int cdgrab_herding_bound(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *z,
                          const int32_t *perm, double *bound_out);
-
-/* Measurement aid, not part of the method: the HBM read bandwidth a plain streaming
- * kernel (non-temporal 16-byte loads, no arithmetic) reaches on this device over a
- * scratch buffer of `bytes` bytes, in GB/s (host double).  Allocates and frees the
- * buffer, synchronises.  Errors: EINVAL (bytes outside 1 MiB .. 64 GiB), ENOMEM, EHIP. */
-int cdgrab_measure_read_bandwidth(cdgrab_handle *h, int64_t bytes, double *gb_per_s_out /*host*/);
 
 /* Timings of the last cdgrab_balance_epoch on this handle (options.timing >= 1).
  * Synchronises the stream.  Errors: EINVAL (timing was off), EHIP. */

@@ -11,6 +11,7 @@ from .cdgrab import (  # noqa: F401
     cdgrab_balance_epoch_independent,
     cdgrab_balance_epoch_randomized,
     cdgrab_balance_epoch_stale_mean,
+    cdgrab_balance_epoch_static,
     cdgrab_herding_bound,
     cdgrab_pergrad,
     cdgrab_plan_epoch,

@@ -102,8 +102,8 @@ def load_library():
     lib.cdgrab_train_softmax.restype = ctypes.c_int
     lib.cdgrab_herding_bound.argtypes = [P, i64, i64, i64, P, P, P]
     lib.cdgrab_herding_bound.restype = ctypes.c_int
-    lib.cdgrab_measure_read_bandwidth.argtypes = [P, i64, ctypes.POINTER(ctypes.c_double)]
-    lib.cdgrab_measure_read_bandwidth.restype = ctypes.c_int
+    lib.cdgrab_balance_epoch_static.argtypes = [P, i64, i64, i64, P, P, P, P, P, P, P]
+    lib.cdgrab_balance_epoch_static.restype = ctypes.c_int
     lib.cdgrab_get_timing.argtypes = [P, ctypes.POINTER(Timing)]
     lib.cdgrab_get_timing.restype = ctypes.c_int
     _lib = lib
@@ -171,12 +171,6 @@ class Handle:
         if rc != CDGRAB_OK:
             raise CdgrabError(rc, self._lib.cdgrab_last_error(self._h).decode())
 
-    def measure_read_bandwidth(self, nbytes: int = 2 << 30) -> float:
-        """GB/s of a plain streaming read over a scratch buffer (the practical ceiling)."""
-        out = ctypes.c_double()
-        self._check(self._lib.cdgrab_measure_read_bandwidth(self._h, nbytes, ctypes.byref(out)))
-        return out.value
-
     def timing(self) -> dict:
         t = Timing()
         self._check(self._lib.cdgrab_get_timing(self._h, ctypes.byref(t)))
@@ -228,6 +222,25 @@ def cdgrab_balance_epoch(h: Handle, m: int, n: int, d: int,
         r64.data_ptr() if r64 is not None else None,
         dots.data_ptr() if dots is not None else None))
     return {"signs": signs, "perm": perm, "r32": r32, "r64": r64, "dots": dots}
+
+
+def cdgrab_balance_epoch_static(h: Handle, grads: torch.Tensor, out: dict,
+                                perm_in: Optional[torch.Tensor] = None) -> dict:
+    """cdgrab_balance_epoch on the library's static workspace (dense input, rows of at most
+    CDGRAB_STATIC_MAX_D elements).  The call allocates nothing: ``out`` holds the caller's
+    output tensors ``signs`` [m][n/2] int8 and ``perm`` [m][n] int32, and optionally ``r32``
+    [d] float32, ``r64`` [d] float64, ``dots`` [m][n/2] float64."""
+    m, n, d = grads.shape
+    dev = h.device
+    h._check(h._lib.cdgrab_balance_epoch_static(
+        h._h, m, n, d, _ptr(grads, torch.float32, (m, n, d), "grads", dev),
+        _ptr(perm_in, torch.int32, (m, n), "perm_in", dev),
+        _ptr(out["signs"], torch.int8, (m, n // 2), "signs", dev),
+        _ptr(out["perm"], torch.int32, (m, n), "perm", dev),
+        _ptr(out.get("r32"), torch.float32, (d,), "r32", dev),
+        _ptr(out.get("r64"), torch.float64, (d,), "r64", dev),
+        _ptr(out.get("dots"), torch.float64, (m, n // 2), "dots", dev)))
+    return out
 
 
 def cdgrab_reorder(h: Handle, signs: torch.Tensor, perm_in: Optional[torch.Tensor] = None) -> torch.Tensor:

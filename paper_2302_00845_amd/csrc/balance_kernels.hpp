@@ -758,22 +758,6 @@ __global__ __launch_bounds__(kThreads) void resolve_dots_apply_split(
 }
 
 // ---------------------------------------------------------------------------
-// Plain streaming read (non-temporal 16 B loads, nothing else): the practical HBM
-// read ceiling against which the passes' achieved bandwidth can be set.
-__global__ __launch_bounds__(kThreads) void stream_read_probe(const float4_t *__restrict__ p, int64_t count4,
-                                                              float *__restrict__ sink)
-{
-    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    float acc = 0.f;
-    for (; i < count4; i += stride) {
-        float4_t v = __builtin_nontemporal_load(p + i);
-        acc += v.x + v.y + v.z + v.w;
-    }
-    if (acc == 1234.5678f) sink[0] = acc;  // keeps the loads; never true for a zero-filled buffer
-}
-
-// ---------------------------------------------------------------------------
 // Clears `count` 32-bit words.  The library clears its flags and scratch with fill
 // kernels rather than memset nodes, so that a caller may capture its stream in a graph.
 __global__ void fill_zero_b32(uint32_t *p, int64_t count) {

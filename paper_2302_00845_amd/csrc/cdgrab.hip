@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -58,6 +59,7 @@ struct cdgrab_handle {
     double *dot_partials = nullptr; int64_t dot_partials_cap = 0;  // its per-workgroup dots of one block
     RowMap *maps = nullptr; int64_t maps_cap = 0;         // its row maps (device)
     float *staging = nullptr;  int64_t staging_cap = 0;   // floats: two staging chunks (the fused pass reads the previous block too)
+    bool fixed_workspace = false;                         // the workspace pointers are borrowed: never grow or free them
 
     std::vector<hipEvent_t> event_pool;
     std::vector<Mark> marks;
@@ -86,6 +88,13 @@ int fail(cdgrab_handle *h, int code, const char *fmt, ...) {
     } while (0)
 
 int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
+
+// Do the byte ranges [a, a + na) and [b, b + nb) share a byte?  (Null ranges never do.)
+bool ranges_overlap(const void *a, int64_t na, const void *b, int64_t nb) {
+    if (!a || !b || na <= 0 || nb <= 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
+}
 
 int pick_vector_width(int64_t d, int64_t base_align) {
     if (d % 4 == 0 && base_align % 16 == 0) return 4;
@@ -126,15 +135,20 @@ int part_size(int bb) {
     return bb == 64 ? PartLayout<64>::PART : bb == 32 ? PartLayout<32>::PART : PartLayout<16>::PART;
 }
 
+// The launch plan of one epoch.  `chunk_pairs` is the number of flattened pairs staged per
+// generator call (streamed input; 0 = one block).  Every decision an epoch takes is taken
+// here, so that cdgrab_plan_epoch reports exactly what a handle with the same options runs.
 int plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs, int32_t streamed,
-               int64_t base_align, int num_cu, int32_t pass1_groups_opt, cdgrab_plan *plan) {
+               int64_t base_align, int num_cu, int32_t pass1_groups_opt, int apply_mode, int gram_mode,
+               int64_t chunk_pairs, cdgrab_plan *plan) {
     if (m < 1 || n < 2 || (n & 1) || d < 1 || !plan) return CDGRAB_EINVAL;
     if (block_pairs != 0 && block_pairs != 16 && block_pairs != 32 && block_pairs != 64) return CDGRAB_EINVAL;
     if (base_align < 4 || (base_align & (base_align - 1))) return CDGRAB_EINVAL;
     if (m > (INT64_MAX / n) / d || m > (1 << 30)) return CDGRAB_EINVAL;
     plan->pairs = m * (n / 2);
     plan->block_pairs = pick_block_pairs(plan->pairs, d, block_pairs);
-    plan->blocks = (plan->pairs + plan->block_pairs - 1) / plan->block_pairs;
+    const int64_t bb = plan->block_pairs;
+    plan->blocks = (plan->pairs + bb - 1) / bb;
     plan->vector_width = pick_vector_width(d, streamed ? 256 : base_align);
     // long rows stream through 128-element tiles with two resident workgroups per CU;
     // short rows use 64-element tiles so that more workgroups share the work
@@ -144,18 +158,44 @@ int plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs, int32_t str
                                         : (int64_t)num_cu * (plan->tile_elems == 128 ? 2 : 4);
     plan->pass1_groups = (int32_t)std::max<int64_t>(1, std::min<int64_t>(want, ntiles));
     plan->pass2_groups = (int32_t)((d + kThreads * 4 - 1) / (kThreads * 4));
-    // with the fused launch two staging blocks: it reads the previous block's rows as well
-    const bool fused = fuse_apply_by_default(d);
+    if (chunk_pairs <= 0) chunk_pairs = bb;
+
+    // Grams ahead: asked for, or chosen for short rows when the caller left both choices
+    // open; for streamed rows when a staging chunk holds several whole blocks.
+    const bool ahead_dense = !streamed && plan->blocks >= 2 &&
+                             (gram_mode == 2 || (gram_mode == 0 && apply_mode == 0 &&
+                                                 gram_ahead_by_default(d, plan->blocks, false)));
+    const bool ahead_streamed = streamed && gram_mode != 1 && apply_mode == 0 && d <= kGramAheadMaxD &&
+                                plan->pairs > bb && chunk_pairs >= 2 * bb && chunk_pairs % bb == 0 &&
+                                chunk_pairs / bb <= kGramBatch;
+    const bool ahead = ahead_dense || ahead_streamed;
+    // the ahead form applies a block inside the next block's launch by construction
+    const bool fused = !ahead && (apply_mode == 2 || (apply_mode == 0 && fuse_apply_by_default(d)));
+    plan->gram_ahead = ahead ? 1 : 0;
     plan->fused_apply = fused ? 1 : 0;
-    plan->staging_bytes = streamed ? (fused ? 2 : 1) * (int64_t)plan->block_pairs * 2 * d * 4 : 0;
-    plan->workspace_bytes = round_up(d, kPadE) * 8 +
-                            (int64_t)plan->pass1_groups * part_size(plan->block_pairs) * 8 +
-                            plan->staging_bytes;
-    plan->bytes_per_example = 8.0 * (double)d + (fused ? 8.0 : 12.0) * (double)d / plan->block_pairs;
-    plan->gram_ahead = gram_ahead_by_default(d, plan->blocks, streamed != 0) ? 1 : 0;
     plan->reserved = 0;
-    // rows read once for the Grams and twice on the chain (as this block, then as the previous one)
-    if (plan->gram_ahead) plan->bytes_per_example = 12.0 * (double)d + 8.0 * (double)d / plan->block_pairs;
+
+    // two staging chunks when a launch reads the previous block's rows as well
+    plan->staging_bytes = streamed ? ((fused || ahead) ? 2 : 1) * chunk_pairs * 2 * d * 4 : 0;
+    const int64_t part = part_size(plan->block_pairs);
+    int64_t partial_doubles = (int64_t)plan->pass1_groups * part;
+    int64_t ahead_bytes = 0;
+    if (ahead) {
+        const int64_t batch = streamed ? chunk_pairs / bb : std::min<int64_t>(plan->blocks, kGramBatch);
+        const int64_t gg = std::max<int64_t>(1, std::min<int64_t>(ntiles, (4 * (int64_t)num_cu + batch - 1) / batch));
+        partial_doubles = std::max(partial_doubles, batch * gg * part);
+        ahead_bytes = (batch + 1) * part * 8                               // reduced Gram tiles
+                      + 2 * ((d + kSplitElems - 1) / kSplitElems * bb) * 8  // per-workgroup dots, two blocks
+                      + batch * (int64_t)sizeof(RowMap);                    // row maps
+    }
+    plan->workspace_bytes = round_up(d, kPadE) * 8 + partial_doubles * 8 +
+                            (int64_t)kReduceSlices * PartLayout<64>::PART * 8 + 64 + ahead_bytes +
+                            plan->staging_bytes;
+    // each row twice; the double running sum read twice and written once per block, or read
+    // once and written once when the apply rides in the next block's launch; with the Gram
+    // matrices ahead the rows are read three times
+    plan->bytes_per_example = ahead ? 12.0 * (double)d + 8.0 * (double)d / (double)bb
+                                    : 8.0 * (double)d + (fused ? 8.0 : 12.0) * (double)d / (double)bb;
     return CDGRAB_OK;
 }
 
@@ -183,6 +223,9 @@ int mark(cdgrab_handle *h, int kind_after) {
 template <typename T>
 int ensure(cdgrab_handle *h, T *&ptr, int64_t &cap, int64_t want) {
     if (cap >= want) return CDGRAB_OK;
+    if (h->fixed_workspace)
+        return fail(h, CDGRAB_ENOMEM, "the fixed workspace is too small (%lld elements needed, %lld there)",
+                    (long long)want, (long long)cap);
     if (ptr) { HIP_TRY(h, hipStreamSynchronize(h->stream)); HIP_TRY(h, hipFree(ptr)); ptr = nullptr; cap = 0; }
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&ptr), (size_t)want * sizeof(T));
     if (e != hipSuccess) {
@@ -440,7 +483,7 @@ const char *cdgrab_last_error(const cdgrab_handle *h) {
 
 int cdgrab_plan_epoch(int64_t m, int64_t n, int64_t d, int32_t block_pairs, int32_t streamed,
                       int64_t base_align, cdgrab_plan *plan) {
-    return plan_epoch(m, n, d, block_pairs, streamed, base_align, 256, 0, plan);
+    return plan_epoch(m, n, d, block_pairs, streamed, base_align, 256, 0, 0, 0, 0, plan);
 }
 
 int cdgrab_pergrad(cdgrab_handle *h, int64_t N, int64_t in_dim, int64_t classes, const float *X,
@@ -540,26 +583,19 @@ int Epoch::prepare() {
         align = (a % 16 == 0) ? 16 : (a % 8 == 0) ? 8 : 4;
         if (a % 4) return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: grads is not 4-byte aligned");
     }
-    int rc = plan_epoch(m, n, d, h->block_pairs_opt, streamed, align, h->num_cu, h->pass1_groups_opt, &plan);
+    // (Every one of the d/64 workgroups of a block's launch in the Grams-ahead form reads all
+    // d/64 x Bb partial dots of the previous block: quadratic in d, hence refused for long rows.)
+    if (h->gram_mode == 2 && !streamed && d > kGramAheadLimitD)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: gram_mode 2 is for rows up to %lld elements (d=%lld)",
+                    (long long)kGramAheadLimitD, (long long)d);
+    int rc = plan_epoch(m, n, d, h->block_pairs_opt, streamed, align, h->num_cu, h->pass1_groups_opt,
+                        h->apply_mode, h->gram_mode, chunk_pairs, &plan);
     if (rc != CDGRAB_OK) return fail(h, rc, "cdgrab_balance_epoch: sizes overflow or are invalid");
     bb = plan.block_pairs;
     if (chunk_pairs <= 0) chunk_pairs = bb;
     staging_chunk = chunk_pairs * 2 * d;
-    fused = h->apply_mode == 2 || (h->apply_mode == 0 && fuse_apply_by_default(d));
-
-    // Grams ahead: asked for, or chosen for short rows when the caller left both choices open.
-    // (Every one of the d/64 workgroups of a block's launch reads all d/64 x Bb partial dots of the
-    // previous block: quadratic in d, which is why the form is refused for long rows.)
-    if (h->gram_mode == 2 && !streamed && d > kGramAheadLimitD)
-        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: gram_mode 2 is for rows up to %lld elements (d=%lld)",
-                    (long long)kGramAheadLimitD, (long long)d);
-    const bool ahead_dense = !streamed && plan.blocks >= 2 &&
-                             (h->gram_mode == 2 || (h->gram_mode == 0 && h->apply_mode == 0 && plan.gram_ahead));
-    // the same for short streamed rows when a staging chunk holds several whole blocks
-    const bool ahead_streamed = streamed && h->gram_mode != 1 && h->apply_mode == 0 && d <= kGramAheadMaxD &&
-                                plan.pairs > bb && chunk_pairs >= 2 * bb && chunk_pairs % bb == 0 &&
-                                chunk_pairs / bb <= kGramBatch;
-    ahead = ahead_dense || ahead_streamed;
+    fused = plan.fused_apply != 0;
+    ahead = plan.gram_ahead != 0;
     batch = streamed ? chunk_pairs / bb : std::min<int64_t>(plan.blocks, kGramBatch);
 
     // workspace
@@ -740,6 +776,9 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     Epoch ep{h, m, n, d, grads, gen, gen_ctx, chunk_pairs, center_row, signs_out, dots_out};
     int rc = ep.prepare();
     if (rc) return rc;
+    // the permutation kernel reads perm_in while other threads write perm_out
+    if (ranges_overlap(perm_in, m * n * 4, perm_out, m * n * 4))
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: perm_in and perm_out must not overlap");
 
     h->marks.clear();
     h->events_used = 0;
@@ -778,6 +817,90 @@ int cdgrab_balance_epoch(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
                               r64_out, dots_out);
 }
 
+// ---- the epoch on a static workspace (for callers that cannot allocate) -------------
+namespace {
+
+// Workspace of cdgrab_balance_epoch_static, in doubles: the running sum, the per-workgroup
+// partials of the dot/Gram pass, the slice sums of the reduction, and the block's signs.
+constexpr int64_t kStaticMaxD = CDGRAB_STATIC_MAX_D;
+constexpr int kStaticGroups = 128;  // workgroups of the dot/Gram pass at most
+constexpr int64_t kStaticRsum = kStaticMaxD;
+constexpr int64_t kStaticPartials = (int64_t)kStaticGroups * PartLayout<64>::PART;
+constexpr int64_t kStaticReduced = (int64_t)kReduceSlices * PartLayout<64>::PART;
+constexpr int64_t kStaticEps = 64 / 8;
+constexpr int64_t kStaticDoubles = kStaticRsum + kStaticPartials + kStaticReduced + kStaticEps;
+static_assert(kStaticMaxD % kPadE == 0, "the running sum is padded to whole tiles");
+
+constexpr int kMaxDevices = 64;
+double *g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, once resolved
+std::mutex g_scratch_mutex;
+
+}  // namespace
+
+// Every GPU the library runs on holds its own copy of this array (about 3.9 MB) until the
+// process ends.  In host code the name is only a stand-in: its device address comes from
+// hipGetSymbolAddress with that device current.
+static __device__ __align__(256) double scratch[kStaticDoubles];
+
+namespace {
+
+int static_scratch(cdgrab_handle *h, double **out) {
+    if (h->device < 0 || h->device >= kMaxDevices)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_static: device ordinal %d not supported", h->device);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[h->device]) {
+        HIP_TRY(h, hipSetDevice(h->device));
+        void *ptr = nullptr;
+        HIP_TRY(h, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(h, CDGRAB_EHIP, "cdgrab_balance_epoch_static: no device address for the workspace");
+        g_scratch_ptr[h->device] = static_cast<double *>(ptr);
+    }
+    *out = g_scratch_ptr[h->device];
+    return CDGRAB_OK;
+}
+
+}  // namespace
+
+int cdgrab_balance_epoch_static(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, const float *grads,
+                                const int32_t *perm_in, int8_t *signs_out, int32_t *perm_out,
+                                float *r_out, double *r64_out, double *dots_out) {
+    if (!h) return CDGRAB_EINVAL;
+    if (!grads) return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_static: grads is NULL (dense input only)");
+    if (d > kStaticMaxD)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_static: d=%lld exceeds the static workspace (at most %lld)",
+                    (long long)d, (long long)kStaticMaxD);
+    double *base = nullptr;
+    int rc = static_scratch(h, &base);
+    if (rc) return rc;
+
+    // Borrow the static array as the handle's workspace for this call: the per-block launch
+    // form, no timing events, at most kStaticGroups workgroups in the dot/Gram pass.
+    struct Saved {
+        double *r_sum, *partials, *reduced; int8_t *eps_blk;
+        int64_t r_cap, partials_cap; int timing, gram_mode, pass1_groups_opt; bool fixed;
+    } sv{h->r_sum, h->partials, h->reduced, h->eps_blk, h->r_cap, h->partials_cap,
+         h->timing, h->gram_mode, h->pass1_groups_opt, h->fixed_workspace};
+    h->r_sum = base;
+    h->r_cap = d > 0 ? round_up(d, kPadE) : 0;  // only this much is cleared and used
+    h->partials = base + kStaticRsum;
+    h->partials_cap = kStaticPartials;
+    h->reduced = h->partials + kStaticPartials;
+    h->eps_blk = reinterpret_cast<int8_t *>(h->reduced + kStaticReduced);
+    h->fixed_workspace = true;
+    h->timing = 0;
+    h->gram_mode = 1;
+    h->pass1_groups_opt = (sv.pass1_groups_opt > 0 && sv.pass1_groups_opt < kStaticGroups) ? sv.pass1_groups_opt
+                                                                                            : kStaticGroups;
+    rc = balance_epoch_impl(h, m, n, d, grads, nullptr, nullptr, 0, perm_in, signs_out, perm_out, r_out,
+                            r64_out, dots_out);
+    h->r_sum = sv.r_sum; h->partials = sv.partials; h->reduced = sv.reduced; h->eps_blk = sv.eps_blk;
+    h->r_cap = sv.r_cap; h->partials_cap = sv.partials_cap;
+    h->timing = sv.timing; h->gram_mode = sv.gram_mode; h->pass1_groups_opt = sv.pass1_groups_opt;
+    h->fixed_workspace = sv.fixed;
+    h->have_timing = false;
+    return rc;
+}
+
 int cdgrab_balance_epoch_randomized(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                                     const float *grads, const float *uniforms, const int32_t *perm_in,
                                     int8_t *signs_out, int32_t *perm_out, double *r64_out,
@@ -800,6 +923,10 @@ int cdgrab_balance_epoch_stale_mean(cdgrab_handle *h, int64_t n, int64_t d, cons
         return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_stale_mean: need n>=1, d>=1");
     if (!grads || !signs_out || !perm_out)
         return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_stale_mean: null pointer");
+    if (ranges_overlap(perm_in, n * 4, perm_out, n * 4))
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_stale_mean: perm_in and perm_out must not overlap");
+    if (ranges_overlap(stale_mean, d * 4, mean_out, d * 4))
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_stale_mean: stale_mean and mean_out must not overlap");
     HIP_TRY(h, hipSetDevice(h->device));
     int rc = CDGRAB_OK;
     if (!stale_mean) {
@@ -889,6 +1016,8 @@ int cdgrab_train_epoch_softmax(cdgrab_handle *h, int64_t m, int64_t n, int64_t i
         return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: bad sizes");
     if (!X || !y || !W || !signs_out || !perm_out)
         return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: null pointer");
+    if (ranges_overlap(perm_in, m * n * 4, perm_out, m * n * 4))
+        return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: perm_in and perm_out must not overlap");
     if (momentum != 0.0f && !velocity)
         return fail(h, CDGRAB_EINVAL, "cdgrab_train_epoch_softmax: momentum needs a velocity buffer");
     HIP_TRY(h, hipSetDevice(h->device));
@@ -946,6 +1075,8 @@ int cdgrab_reorder(cdgrab_handle *h, int64_t m, int64_t n, const int8_t *signs,
     if (m < 1 || n < 1 || n > INT32_MAX || m > INT32_MAX)
         return fail(h, CDGRAB_EINVAL, "cdgrab_reorder: need m>=1, n>=1");
     if (!signs || !perm_out) return fail(h, CDGRAB_EINVAL, "cdgrab_reorder: null pointer");
+    if (ranges_overlap(perm_in, m * n * 4, perm_out, m * n * 4))
+        return fail(h, CDGRAB_EINVAL, "cdgrab_reorder: perm_in and perm_out must not overlap");
     HIP_TRY(h, hipSetDevice(h->device));
     if (!h->flag) { int64_t cap = 0; int rc = ensure(h, h->flag, cap, (int64_t)1); if (rc) return rc; }
     hipLaunchKernelGGL(fill_zero_b32, dim3(1), dim3(64), 0, h->stream, reinterpret_cast<uint32_t *>(h->flag), (int64_t)1);
@@ -1000,39 +1131,6 @@ int cdgrab_herding_bound(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
     else if (vw == 2) launch(std::integral_constant<int, 2>{});
     else launch(std::integral_constant<int, 1>{});
     HIP_TRY(h, hipGetLastError());
-    return CDGRAB_OK;
-}
-
-int cdgrab_measure_read_bandwidth(cdgrab_handle *h, int64_t bytes, double *gb_per_s_out) {
-    if (!h || !gb_per_s_out) return CDGRAB_EINVAL;
-    if (bytes < (1 << 20) || bytes > ((int64_t)64 << 30))
-        return fail(h, CDGRAB_EINVAL, "cdgrab_measure_read_bandwidth: bytes must be between 1 MiB and 64 GiB");
-    HIP_TRY(h, hipSetDevice(h->device));
-    const int64_t count4 = bytes / 16;
-    float *buf = nullptr;
-    if (hipMalloc(reinterpret_cast<void **>(&buf), (size_t)count4 * 16 + 16) != hipSuccess) {
-        (void)hipGetLastError();
-        return fail(h, CDGRAB_ENOMEM, "cdgrab_measure_read_bandwidth: cannot allocate %lld bytes", (long long)bytes);
-    }
-    hipEvent_t e0, e1;
-    HIP_TRY(h, hipEventCreate(&e0));
-    HIP_TRY(h, hipEventCreate(&e1));
-    HIP_TRY(h, hipMemsetAsync(buf, 0, (size_t)count4 * 16 + 16, h->stream));
-    const int reps = 5;
-    const dim3 grid((unsigned)(h->num_cu * 8));
-    const float4_t *src = reinterpret_cast<const float4_t *>(buf);
-    hipLaunchKernelGGL(stream_read_probe, grid, dim3(kThreads), 0, h->stream, src, count4, buf + count4 * 4);
-    HIP_TRY(h, hipEventRecord(e0, h->stream));
-    for (int q = 0; q < reps; ++q)
-        hipLaunchKernelGGL(stream_read_probe, grid, dim3(kThreads), 0, h->stream, src, count4, buf + count4 * 4);
-    HIP_TRY(h, hipEventRecord(e1, h->stream));
-    HIP_TRY(h, hipEventSynchronize(e1));
-    float ms = 0.f;
-    HIP_TRY(h, hipEventElapsedTime(&ms, e0, e1));
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    HIP_TRY(h, hipFree(buf));
-    *gb_per_s_out = (double)count4 * 16.0 * reps / ((double)ms * 1e-3) / 1e9;
     return CDGRAB_OK;
 }
 

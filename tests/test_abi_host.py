@@ -32,7 +32,7 @@ def test_header_declares_the_expected_calls():
     for required in ("cdgrab_pergrad", "cdgrab_balance_epoch", "cdgrab_reorder", "cdgrab_create",
                      "cdgrab_destroy", "cdgrab_last_error", "cdgrab_plan_epoch", "cdgrab_get_timing",
                      "cdgrab_herding_bound", "cdgrab_train_epoch_softmax", "cdgrab_train_softmax",
-                     "cdgrab_balance_epoch_independent", "cdgrab_measure_read_bandwidth",
+                     "cdgrab_balance_epoch_independent",
                      "cdgrab_balance_epoch_stale_mean", "cdgrab_balance_epoch_randomized"):
         assert required in names
 
@@ -63,8 +63,18 @@ def test_plan_epoch_headline_shapes(p):
     c2 = p.cdgrab_plan_epoch(16, 3750, 7850)
     assert c2["pairs"] == 30000 and c2["block_pairs"] == 64 and c2["blocks"] == 469 and c2["vector_width"] == 2
     assert c2["staging_bytes"] == 0
-    # short dense rows: Gram matrices ahead, rows read three times
+    # short dense rows: Gram matrices ahead, rows read three times; that form applies a block
+    # inside its own launch, so it is not reported as the fused dot/Gram launch
     assert c2["gram_ahead"] == 1 and c2["bytes_per_example"] == 12 * 7850 + 8 * 7850 / 64
+    assert c2["fused_apply"] == 0
+    # its workspace counts the buffers of that form: reduced Gram tiles of 469 blocks (+1 carried
+    # over), two blocks' per-workgroup dots, the row maps, and partials for all blocks' workgroups
+    part = 10 * 256 + 64
+    groups = -(-4 * 256 // 469)
+    assert c2["workspace_bytes"] >= 469 * groups * part * 8 + 470 * part * 8 + 2 * 123 * 64 * 8
+    # long streamed rows: running sum + partials of 512 workgroups + one staging block
+    assert c4["workspace_bytes"] >= 11_200_000 * 8 + 512 * (3 * 256 + 32) * 8 + c4["staging_bytes"]
+    assert c4["workspace_bytes"] < 11_200_128 * 8 + 512 * (3 * 256 + 32) * 8 + c4["staging_bytes"] + (1 << 20)
     assert c4["gram_ahead"] == 0 and c3["gram_ahead"] == 0
     assert p.cdgrab_plan_epoch(16, 3750, 7850, streamed=True)["gram_ahead"] == 0
     assert p.cdgrab_plan_epoch(4, 64, 100_000)["gram_ahead"] == 0

@@ -312,6 +312,48 @@ def test_parallel_herding_closed_form():
     assert oracle.parallel_herding(z + 5.0) == 3.0
 
 
+def _load_herding_cases():
+    cases, cur = [], None
+    for line in open(os.path.join(GOLDEN, "herding_cases.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, *vals = line.split()
+        if key == "case":
+            cur = {"name": vals[0], "m": int(vals[1]), "n": int(vals[2]), "d": int(vals[3])}
+            cases.append(cur)
+        elif key == "z":
+            cur["z"] = np.array([float(v) for v in vals], np.float32).reshape(cur["m"], cur["n"], cur["d"])
+        elif key == "perm":
+            cur["perm"] = None if vals == ["-"] else np.array([int(v) for v in vals], np.int32).reshape(
+                cur["m"], cur["n"])
+        elif key == "bound":
+            cur["bound"] = float(vals[0])
+        elif key == "others":
+            cur["others"] = [float(v) for v in vals]
+    return cases
+
+
+@pytest.mark.parametrize("case", _load_herding_cases(), ids=lambda c: c["name"])
+def test_parallel_herding_hand_cases_fix_the_norm(case):
+    """d = 2 cases worked by hand from the definition (Sec. 3.2): the objective takes the
+    max norm of every prefix sum.  The Euclidean and the 1-norm give other numbers on the
+    decisive prefix (listed in the file), so the choice of norm is pinned for d > 1."""
+    got = oracle.parallel_herding(case["z"], case["perm"])
+    assert got == case["bound"]
+    # the listed alternatives are what the other norms give: recomputed here directly
+    z = case["z"].astype(np.float64)
+    m, n, d = z.shape
+    perm = case["perm"] if case["perm"] is not None else np.tile(np.arange(n), (m, 1))
+    centred = z - z.reshape(-1, d).mean(0)
+    prefix = np.cumsum(sum(centred[i, perm[i]] for i in range(m)), axis=0)
+    assert np.abs(prefix).max() == case["bound"]
+    l2, l1 = np.linalg.norm(prefix, axis=1).max(), np.abs(prefix).sum(1).max()
+    assert abs(l2 - case["others"][0]) < 1e-12 and abs(l1 - case["others"][1]) < 1e-12
+    if case["name"] != "PD":
+        assert l2 != case["bound"] and l1 != case["bound"]
+
+
 def test_reordering_lowers_herding_objective_on_average():
     """Soft check of the purpose of the method (Lemma 1): over a few rounds of
     balance+reorder on fixed vectors the parallel herding objective drops well
@@ -503,3 +545,44 @@ def test_randomized_epoch_respects_the_balance_bound():
     t_c = -out["t"][0]                                          # <r, c>
     forced = np.abs(t_c) > 1.0
     assert np.all(s[forced] == -np.sign(t_c[forced]))
+
+
+# --------------------------------------------------------------------------- replay links
+def test_stale_mean_walk_is_the_pair_walk_over_vector_and_mean():
+    """Centralized balancing of g_j - mean equals the pair walk over the pairs (g_j, mean)
+    with exported sign -s_j (difference mean - g_j = -z_j): two separately written oracle
+    functions agree, which is what the GPU tests' replay after a near-tie relies on."""
+    from parity import judge_greedy, replay_pairs
+    rng = np.random.default_rng(3)
+    n, d = 65, 40
+    g = workloads.heavy_rows(3, 1, n, d)[0]
+    mu = (g.mean(0) + 0.01 * rng.standard_normal(d)).astype(np.float32)
+    ref = oracle.grab_stale_mean(g, mu)
+    rows = np.stack([g, np.broadcast_to(mu, g.shape)], axis=1)
+    r, t, nr, nz = replay_pairs(rows, -ref["s"])
+    assert np.array_equal(r, ref["r"])
+    np.testing.assert_allclose(t, -ref["t"], rtol=0, atol=1e-12 * (nr * nz).max())
+    assert judge_greedy(t, nr, nz, -ref["s"]) == 0
+    # an imposed wrong sign outside the margin is caught
+    wrong = -ref["s"].copy()
+    k = int(np.argmax(np.abs(ref["t"])))
+    wrong[k] = -wrong[k]
+    r2, t2, nr2, nz2 = replay_pairs(rows, wrong)
+    with pytest.raises(AssertionError):
+        judge_greedy(t2, nr2, nz2, wrong)
+
+
+def test_randomized_walk_replays_through_the_pair_walk():
+    from parity import flatten_pairs, replay_pairs
+    rng = np.random.default_rng(4)
+    m, n, d = 3, 30, 50
+    v = rng.standard_normal((m, n, d))
+    z = (v / (2 * np.linalg.norm(v, axis=2, keepdims=True))).astype(np.float32)
+    u = rng.random((m, n // 2)).astype(np.float32)
+    ref = oracle.randomized_epoch(z, u)
+    flat = np.ascontiguousarray(ref["eps"].T).reshape(-1)
+    r, t, nr, nc = replay_pairs(flatten_pairs(z), flat)
+    assert np.array_equal(r, ref["r"])
+    assert np.array_equal(t.reshape(n // 2, m).T, ref["t"])
+    uf = np.ascontiguousarray(u.T).reshape(-1).astype(np.float64)
+    assert np.array_equal(np.where(uf < 0.5 * (1.0 + t), -1, 1), flat)
