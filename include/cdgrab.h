@@ -49,7 +49,11 @@ typedef struct cdgrab_options {
     int32_t apply_mode;  /* how r += sum eps_k d_k of a block is launched: 1 = its own
                             apply launch after the block is resolved; 2 = inside the next
                             block's dot/Gram launch (one streaming launch per block, the
-                            running sum read once per block); 0 = choose by row length  */
+                            running sum read once per block); 0 = choose by row length.
+                            3 / 4 = as 1 with the choice of the apply kernel taken away:
+                            3 = always the kernel for long rows (a resident grid that updates
+                            the running sum in one burst at the end of the launch), 4 = always
+                            the flat kernel (one thread per four elements)                 */
     int32_t gram_mode;   /* dense input (and the staged rows of cdgrab_train_epoch_softmax).
                             1 = every block computes its Gram matrix in
                             its own dot/Gram launch; 2 = the Gram matrices of up to 512
@@ -58,6 +62,7 @@ typedef struct cdgrab_options {
                             block's resolver and apply, this block's dots); refused
                             (EINVAL) for d > 131 072; 0 = choose (2 for rows up to 16 384
                             elements when apply_mode is 0 as well)                        */
+    int32_t apply_groups; /* cap on the workgroups of the resident apply kernel; 0 = two per CU */
 } cdgrab_options;
 
 /* Event-timed durations of the last cdgrab_balance_epoch call (timing >= 1);

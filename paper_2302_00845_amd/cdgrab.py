@@ -32,7 +32,7 @@ class _Options(ctypes.Structure):
     _fields_ = [("device", ctypes.c_int32), ("block_pairs", ctypes.c_int32),
                 ("stream", ctypes.c_void_p), ("timing", ctypes.c_int32),
                 ("pass1_groups", ctypes.c_int32), ("apply_mode", ctypes.c_int32),
-                ("gram_mode", ctypes.c_int32)]
+                ("gram_mode", ctypes.c_int32), ("apply_groups", ctypes.c_int32)]
 
 
 class Timing(ctypes.Structure):
@@ -141,7 +141,7 @@ class Handle:
 
     def __init__(self, device: int = 0, block_pairs: int = 0, timing: int = 0,
                  pass1_groups: int = 0, stream: Optional[torch.cuda.Stream] = None,
-                 apply_mode: int = 0, gram_mode: int = 0):
+                 apply_mode: int = 0, gram_mode: int = 0, apply_groups: int = 0):
         self._lib = load_library()
         self.device = torch.device("cuda", device)
         if stream is None:
@@ -149,7 +149,7 @@ class Handle:
         self.stream = stream
         opt = _Options(device=device, block_pairs=block_pairs, stream=stream.cuda_stream,
                        timing=timing, pass1_groups=pass1_groups,
-                       apply_mode=apply_mode, gram_mode=gram_mode)
+                       apply_mode=apply_mode, gram_mode=gram_mode, apply_groups=apply_groups)
         h = ctypes.c_void_p()
         rc = self._lib.cdgrab_create(ctypes.byref(h), ctypes.byref(opt))
         if rc != CDGRAB_OK:

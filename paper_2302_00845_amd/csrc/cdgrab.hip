@@ -39,7 +39,9 @@ struct cdgrab_handle {
     int block_pairs_opt = 0;
     int timing = 0;
     int pass1_groups_opt = 0;
-    int apply_mode = 0;  // 0 choose by row length, 1 separate apply launch, 2 apply fused into the next block's launch
+    int apply_mode = 0;  // 0 choose by row length, 1 separate apply launch, 2 apply fused into the next block's launch,
+                         // 3 / 4 separate launch, always in the resident / the flat form
+    int apply_groups_opt = 0;  // cap on the resident apply grid (0: two workgroups per CU)
     int gram_mode = 0;   // 0 choose, 1 each block's Gram in its own launch, 2 Grams of many blocks ahead in one launch
     int num_cu = 256;
     std::string err;
@@ -263,10 +265,14 @@ void launch_pass1(cdgrab_handle *h, const RowMap &rm, const PrevBlock *prev, con
                                h->r_sum, h->partials, ntiles);
     }
 }
+// Rows from this length on take the resident form of the apply pass (the running-sum
+// traffic in one burst); shorter ones the flat form, whose launch ramps up faster.
+constexpr int64_t kResidentMinD = (int64_t)1 << 21;
+
 template <int BB, int VW>
 void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
     // short rows: too few flat workgroups to hide latency -> split the pairs over thread groups
-    if (groups < 2 * h->num_cu) {
+    if (groups < 2 * h->num_cu && h->apply_mode < 3) {
         const dim3 grid((unsigned)((rm.d + kSplitElems - 1) / kSplitElems));
         if (rm.nb == BB)
             hipLaunchKernelGGL((pass2_apply_split<BB, VW, true>), grid, dim3(kThreads), 0, h->stream, rm,
@@ -274,6 +280,23 @@ void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
         else
             hipLaunchKernelGGL((pass2_apply_split<BB, VW, false>), grid, dim3(kThreads), 0, h->stream, rm,
                                h->eps_blk, h->r_sum);
+        return;
+    }
+    if (h->apply_mode == 3 || (h->apply_mode != 4 && rm.d >= kResidentMinD)) {
+        // a wholly resident grid: two workgroups per CU, each thread up to kResidentGroups groups of four
+        const int64_t quads = (rm.d + 3) / 4;
+        int64_t grid = std::min<int64_t>(2 * (int64_t)h->num_cu, (quads + kThreads - 1) / kThreads);
+        if (h->apply_groups_opt > 0) grid = std::min<int64_t>(grid, h->apply_groups_opt);
+        const int64_t T = grid * kThreads;
+        const int64_t per_thread = (quads + T - 1) / T;
+        const int64_t slabs = (per_thread + kResidentGroups - 1) / kResidentGroups;
+        const int kuse = (int)((per_thread + slabs - 1) / slabs);
+        if (rm.nb == BB)
+            hipLaunchKernelGGL((pass2_apply_resident<BB, VW, true>), dim3((unsigned)grid), dim3(kThreads), 0,
+                               h->stream, rm, h->eps_blk, h->r_sum, kuse, (int)slabs);
+        else
+            hipLaunchKernelGGL((pass2_apply_resident<BB, VW, false>), dim3((unsigned)grid), dim3(kThreads), 0,
+                               h->stream, rm, h->eps_blk, h->r_sum, kuse, (int)slabs);
         return;
     }
     if (rm.nb == BB)
@@ -431,7 +454,9 @@ int cdgrab_create(cdgrab_handle **out, const cdgrab_options *opt) {
     if (o.timing < 0 || o.timing > 2) return fail(nullptr, CDGRAB_EINVAL, "timing must be 0, 1 or 2");
     if (o.pass1_groups < 0 || o.pass1_groups > 65536)
         return fail(nullptr, CDGRAB_EINVAL, "pass1_groups out of range");
-    if (o.apply_mode < 0 || o.apply_mode > 2) return fail(nullptr, CDGRAB_EINVAL, "apply_mode must be 0, 1 or 2");
+    if (o.apply_mode < 0 || o.apply_mode > 4) return fail(nullptr, CDGRAB_EINVAL, "apply_mode must be 0 .. 4");
+    if (o.apply_groups < 0 || o.apply_groups > 65536)
+        return fail(nullptr, CDGRAB_EINVAL, "apply_groups out of range");
     if (o.gram_mode < 0 || o.gram_mode > 2) return fail(nullptr, CDGRAB_EINVAL, "gram_mode must be 0, 1 or 2");
     int count = 0;
     hipError_t e = hipGetDeviceCount(&count);
@@ -447,6 +472,7 @@ int cdgrab_create(cdgrab_handle **out, const cdgrab_options *opt) {
     h->pass1_groups_opt = o.pass1_groups;
     h->apply_mode = o.apply_mode;
     h->gram_mode = o.gram_mode;
+    h->apply_groups_opt = o.apply_groups;
     hipDeviceProp_t prop;
     if (hipSetDevice(h->device) == hipSuccess && hipGetDeviceProperties(&prop, h->device) == hipSuccess)
         h->num_cu = prop.multiProcessorCount;

@@ -21,9 +21,10 @@ def lib():
     return p
 
 
-def run_epoch(p, z, perm_in=None, block_pairs=0, pass1_groups=0, apply_mode=0, gram_mode=0):
+def run_epoch(p, z, perm_in=None, block_pairs=0, pass1_groups=0, apply_mode=0, gram_mode=0, apply_groups=0):
     m, n, d = z.shape
-    h = p.Handle(block_pairs=block_pairs, pass1_groups=pass1_groups, apply_mode=apply_mode, gram_mode=gram_mode)
+    h = p.Handle(block_pairs=block_pairs, pass1_groups=pass1_groups, apply_mode=apply_mode, gram_mode=gram_mode,
+                 apply_groups=apply_groups)
     zt = torch.from_numpy(z).cuda()
     pt = torch.from_numpy(perm_in).cuda() if perm_in is not None else None
     out = p.cdgrab_balance_epoch(h, m, n, d, grads=zt, perm_in=pt, want_r32=True, want_r64=True,
@@ -92,6 +93,42 @@ def test_fused_and_separate_passes_agree(lib, m, n, d, bb):
     z = workloads.heavy_rows(m * n, m, n, d)
     check_epoch(z, run_epoch(lib, z, block_pairs=bb, apply_mode=2))
     check_epoch(z, run_epoch(lib, z, block_pairs=bb, apply_mode=1))
+
+
+@pytest.mark.parametrize("m,n,d,bb,groups", [
+    (4, 64, 1024, 16, 0), (3, 50, 777, 32, 0), (8, 40, 65536 + 12, 32, 0), (16, 30, 130, 64, 0),
+    (2, 70, 30000, 0, 1),        # one workgroup: 30 groups per thread, two slabs of 15
+    (3, 22, 100001, 32, 2),      # odd row length (scalar loads), ragged last block, three slabs
+    (2, 36, 262144 + 8, 16, 0),  # 65 538 groups on 257 workgroups: the last thread row is partly empty
+    (1, 4, 1, 0, 0)])
+def test_resident_apply_matches_flat_apply(lib, m, n, d, bb, groups):
+    """The apply kernel for long rows (a resident grid, sums held in registers, the running
+    sum updated in one burst per slab) adds the same terms in the same order as the flat
+    one: every output is bit-identical, also on rows that are not exactly representable."""
+    for z in (workloads.integer_rows(m + d, m, n, d, 5), workloads.heavy_rows(m * n + 1, m, n, d)):
+        a = run_epoch(lib, z, block_pairs=bb, apply_mode=3, apply_groups=groups)
+        b = run_epoch(lib, z, block_pairs=bb, apply_mode=4)
+        for k in ("signs", "perm", "r64", "r32", "dots"):
+            assert np.array_equal(a[k], b[k]), k
+        check_epoch(z, a)
+
+
+def test_resident_apply_unaligned_rows(lib):
+    """Rows that start at an 8-byte (not 16-byte) boundary take the two-float loads."""
+    m, n, d = 2, 12, 20002
+    z = workloads.heavy_rows(9, m, n, d)
+    buf = torch.zeros(m * n * d + 2, dtype=torch.float32, device="cuda")
+    view = buf[2:].view(m, n, d)
+    view.copy_(torch.from_numpy(z))
+    outs = []
+    for mode in (3, 4):
+        h = lib.Handle(apply_mode=mode, apply_groups=3)
+        out = lib.cdgrab_balance_epoch(h, m, n, d, grads=view, want_r64=True, want_dots=True)
+        torch.cuda.synchronize()
+        outs.append({k: v.cpu().numpy() for k, v in out.items() if v is not None})
+    for k in ("signs", "perm", "r64", "dots"):
+        assert np.array_equal(outs[0][k], outs[1][k]), k
+    check_epoch(z, outs[0])
 
 
 @pytest.mark.parametrize("m,n,d,bb", [(4, 64, 1024, 16), (3, 50, 777, 32), (8, 40, 65536 + 12, 32),

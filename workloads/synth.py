@@ -82,6 +82,8 @@ def _hip_lib():
         lib.synth_fill_pairs_device.restype = ctypes.c_int
         lib.synth_set_drain.argtypes = [ctypes.c_void_p, ctypes.c_int64]
         lib.synth_set_drain.restype = ctypes.c_int
+        lib.synth_set_streaming_stores.argtypes = [ctypes.c_int]
+        lib.synth_set_streaming_stores.restype = ctypes.c_int
         _hip = lib
     return _hip
 
@@ -108,6 +110,19 @@ def set_input_drain(enabled: bool, device: str = "cuda:0", megabytes: int = 384)
         lib.synth_set_drain(_drain_buf.data_ptr(), _drain_buf.numel())
     else:
         lib.synth_set_drain(None, 0)
+
+
+STORE_MODES = {"plain": 0, "streaming": 1, "auto": 2}
+
+
+def set_store_mode(mode: str = "auto") -> None:
+    """How the device generator writes its rows: "plain" (ordinary stores), "streaming"
+    (non-temporal stores) or "auto" (the default: streaming for blocks larger than the
+    last-level cache, plain for blocks that fit it).  The values are the same in every
+    mode; only the cache hint of the stores differs."""
+    rc = _hip_lib().synth_set_streaming_stores(STORE_MODES[mode])
+    if rc != 0:
+        raise ValueError("bad store mode %r" % mode)
 
 
 class SynthRows:

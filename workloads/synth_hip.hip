@@ -7,6 +7,11 @@
 
 namespace {
 
+typedef float syn_f4v __attribute__((ext_vector_type(4)));
+
+// STREAM: the rows are written with streaming (non-temporal) stores, as a producer of
+// write-once data would; otherwise with ordinary stores.
+template <bool STREAM>
 __global__ __launch_bounds__(256) void synth_fill_kernel(synth_params p, uint64_t seed_mixed,
                                                          int64_t first_pair, float *__restrict__ staging)
 {
@@ -31,7 +36,12 @@ __global__ __launch_bounds__(256) void synth_fill_kernel(synth_params p, uint64_
             v[q] = (e + q < p.d) ? syn_element_in_block(&p, seed_mixed, row, e + q, b) : 0.0f;
         }
         if (e + 3 < p.d && (p.d & 3) == 0) {
-            *reinterpret_cast<float4 *>(out + e) = make_float4(v[0], v[1], v[2], v[3]);
+            if constexpr (STREAM) {
+                const syn_f4v val = {v[0], v[1], v[2], v[3]};
+                __builtin_nontemporal_store(val, reinterpret_cast<syn_f4v *>(out + e));
+            } else {
+                *reinterpret_cast<float4 *>(out + e) = make_float4(v[0], v[1], v[2], v[3]);
+            }
         } else {
 #pragma unroll
             for (int q = 0; q < 4; ++q) if (e + q < p.d) out[e + q] = v[q];
@@ -66,6 +76,19 @@ extern "C" int synth_set_drain(float *scratch /*dev or NULL*/, int64_t floats) {
     return 0;
 }
 
+// Store flavour of the fill kernel: 0 ordinary stores, 1 streaming (non-temporal) stores,
+// 2 (default) chosen per block as a producer on the same GPU would: a block that fits the
+// last-level cache (256 MB Infinity Cache + L2) is left cacheable, because the consumer reads
+// it right away; a larger one is streamed, because most of it would only pass through the
+// cache as dirty lines whose write-back then competes with the consumer's reads.
+static int g_streaming_stores = 2;
+static const int64_t kStreamAboveBytes = (int64_t)384 << 20;
+extern "C" int synth_set_streaming_stores(int mode) {
+    if (mode < 0 || mode > 2) return -1;
+    g_streaming_stores = mode;
+    return 0;
+}
+
 extern "C" int synth_fill_pairs_device(void *ctx, int64_t first_pair, int64_t count, float *staging,
                                        void *stream)
 {
@@ -74,8 +97,14 @@ extern "C" int synth_fill_pairs_device(void *ctx, int64_t first_pair, int64_t co
     if (first_pair + count > p->m * (p->n / 2)) return -2;
     int64_t per_row = (p->d + 1023) / 1024;
     unsigned gx = (unsigned)(per_row < 2048 ? per_row : 2048);
-    hipLaunchKernelGGL(synth_fill_kernel, dim3(gx, (unsigned)(2 * count)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), *p, syn_seed_mixed(p->seed), first_pair, staging);
+    const bool stream_stores = g_streaming_stores == 1 ||
+                               (g_streaming_stores == 2 && count * 2 * p->d * 4 > kStreamAboveBytes);
+    if (stream_stores)
+        hipLaunchKernelGGL(synth_fill_kernel<true>, dim3(gx, (unsigned)(2 * count)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), *p, syn_seed_mixed(p->seed), first_pair, staging);
+    else
+        hipLaunchKernelGGL(synth_fill_kernel<false>, dim3(gx, (unsigned)(2 * count)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), *p, syn_seed_mixed(p->seed), first_pair, staging);
     if (g_drain_scratch && g_drain_floats >= 8)
         hipLaunchKernelGGL(synth_drain_kernel, dim3(2048), dim3(256), 0, static_cast<hipStream_t>(stream),
                            reinterpret_cast<const float4 *>(g_drain_scratch), (g_drain_floats - 4) / 4,
