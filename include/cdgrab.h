@@ -234,7 +234,10 @@ int cdgrab_balance_epoch_stale_mean(cdgrab_handle *h, int64_t n, int64_t d, cons
 
 /* The uncoordinated ablation baseline "ID-GraB (PairBal)" (Sec. 5, ablation study):
  * every worker balances its own pairs on its own running sum, with no shared state,
- * i.e. m separate runs of cdgrab_balance_epoch with m = 1.  Same layouts as there:
+ * i.e. m separate runs of cdgrab_balance_epoch with m = 1.  For short rows (where such a
+ * run is a chain of small dependent launches) the m walks run side by side, the worker as
+ * a grid coordinate of every launch; for long rows one after the other.  Either way a
+ * worker's result is that of its own one-worker epoch.  Same layouts as there:
  *   grads [m][n][d] fp32 dev, perm_in [m][n] or NULL, signs_out [m][n/2], perm_out [m][n].
  * Errors: as cdgrab_balance_epoch. */
 int cdgrab_balance_epoch_independent(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,

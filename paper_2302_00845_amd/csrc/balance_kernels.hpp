@@ -151,6 +151,19 @@ struct PrevBlock {
     const int8_t *eps;   // its resolved signs
 };
 
+// Several independent walks of the same shape in one launch (the uncoordinated baseline:
+// every worker balances its own rows on its own running sum).  The walk is a grid
+// coordinate; everything a walk owns lies at a fixed element stride from the first walk's.
+// All strides are zero for a single walk.
+struct WalkStrides {
+    int64_t rows;   // floats from walk w's rows to walk w+1's
+    int64_t r;      // doubles between running sums
+    int64_t gram;   // doubles between the walks' reduced Gram tiles
+    int64_t dots;   // doubles between the walks' per-workgroup dots
+    int64_t out;    // entries between the walks' slices of signs_out / dots_out
+    int64_t maps;   // row maps per walk
+};
+
 // `group` of `ngroups` workgroups share the tiles; the workgroup's result goes to `out`.
 template <int BB, int VW, int TE, bool APPLY, bool NB>
 __device__ __forceinline__ void pass1_body(const RowMap &rm, const PrevBlock &prev, double *__restrict__ r_sum,
@@ -366,29 +379,33 @@ __global__ __launch_bounds__(kThreads) void pass1_dots_gram(RowMap rm, PrevBlock
 template <int BB, int VW, int TE>
 __global__ __launch_bounds__(kThreads) void gram_batched(const RowMap *__restrict__ maps,
                                                          double *__restrict__ r_sum,
-                                                         double *__restrict__ partials, int64_t ntiles)
+                                                         double *__restrict__ partials, int64_t ntiles,
+                                                         int64_t maps_per_walk)
 {
-    const RowMap &rm = maps[blockIdx.y];
+    // blockIdx.z: the walk (its maps follow the previous walk's)
+    const RowMap &rm = maps[(int64_t)blockIdx.z * maps_per_walk + blockIdx.y];
     PrevBlock none;
     none.rm.nb = 0;
     none.eps = nullptr;
-    pass1_body<BB, VW, TE, false, false>(rm, none, r_sum,
-                                  partials + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * PartLayout<BB>::PART,
-                                  ntiles, (int)blockIdx.x, (int)gridDim.x);
+    const int64_t slot = ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    pass1_body<BB, VW, TE, false, false>(rm, none, r_sum, partials + slot * PartLayout<BB>::PART, ntiles,
+                                         (int)blockIdx.x, (int)gridDim.x);
 }
 
 // Sum over the `groups` workgroups of each block of the batched form, in group order:
 // gram_all[b][idx] = sum_g partials[(b * groups + g)][idx].
 __global__ __launch_bounds__(kThreads) void reduce_batched(const double *__restrict__ partials,
-                                                           double *__restrict__ gram_all, int part, int groups)
+                                                           double *__restrict__ gram_all, int part, int groups,
+                                                           int64_t walk_gram_stride)
 {
     const int idx = blockIdx.x * kThreads + threadIdx.x;
     if (idx >= part) return;
-    const double *src = partials + (int64_t)blockIdx.y * groups * part + idx;
+    // blockIdx.y: block of the batch, blockIdx.z: walk
+    const double *src = partials + ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * groups * part + idx;
     double sum = 0.0;
 #pragma unroll 8
     for (int g = 0; g < groups; ++g) sum += src[(int64_t)g * part];
-    gram_all[(int64_t)blockIdx.y * part + idx] = sum;
+    gram_all[(int64_t)blockIdx.z * walk_gram_stride + (int64_t)blockIdx.y * part + idx] = sum;
 }
 
 // ---------------------------------------------------------------------------
@@ -584,11 +601,15 @@ __global__ __launch_bounds__(kResolveThreads<BB>) void resolve_signs(const doubl
                                                                      int8_t *__restrict__ eps_blk,
                                                                      int8_t *__restrict__ signs_out,
                                                                      double *__restrict__ dots_out,
-                                                                     const float *__restrict__ uniforms)
+                                                                     const float *__restrict__ uniforms,
+                                                                     WalkStrides ws)
 {
-    resolve_body<BB, RANDOM, SLICES, kResolveThreads<BB>>(gram_src, gram_stride, dot_src, dot_groups, dot_stride, nb,
-                                                          k0, i0, m, half_n, true, eps_blk, signs_out, dots_out,
-                                                          uniforms, nullptr);
+    const int64_t w = blockIdx.y;  // the walk
+    resolve_body<BB, RANDOM, SLICES, kResolveThreads<BB>>(gram_src + w * ws.gram, gram_stride, dot_src + w * ws.dots,
+                                                          dot_groups, dot_stride, nb, k0, i0, m, half_n, true,
+                                                          eps_blk + w * kMaxBlockPairs, signs_out + w * ws.out,
+                                                          dots_out ? dots_out + w * ws.out : nullptr, uniforms,
+                                                          nullptr);
 }
 
 // ---------------------------------------------------------------------------
@@ -696,10 +717,13 @@ constexpr int kSplitElems = (kThreads / kSplitGroups) * 4;  // 64 elements per w
 
 template <int BB, int VW, bool FULL>
 __global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const int8_t *__restrict__ eps_blk,
-                                                              double *__restrict__ r_sum)
+                                                              double *__restrict__ r_sum, WalkStrides ws)
 {
     __shared__ double part[kSplitGroups][kSplitElems];
     const int64_t d = rm.d;
+    const int64_t woff = (int64_t)blockIdx.y * ws.rows;  // blockIdx.y: the walk
+    eps_blk += (int64_t)blockIdx.y * kMaxBlockPairs;
+    r_sum += (int64_t)blockIdx.y * ws.r;
     const int quad = threadIdx.x % (kThreads / kSplitGroups), grp = threadIdx.x / (kThreads / kSplitGroups);
     const int64_t e = (int64_t)blockIdx.x * kSplitElems + quad * 4;
     const int64_t mine = (int64_t)blockIdx.x * kSplitElems + threadIdx.x;
@@ -712,8 +736,8 @@ __global__ __launch_bounds__(kThreads) void pass2_apply_split(RowMap rm, const i
         const int j = grp * PER + q;
         // (offsets of missing pairs are readable rows: zero, or those of an earlier block)
         const bool have = FULL || j < rm.nb;
-        a[q] = load4_nb<VW>(rm.row(j, 0), have, e, d);
-        b[q] = load4_nb<VW>(rm.row(j, 1), have, e, d);
+        a[q] = load4_nb<VW>(rm.row(j, 0) + woff, have, e, d);
+        b[q] = load4_nb<VW>(rm.row(j, 1) + woff, have, e, d);
     }
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
@@ -753,12 +777,23 @@ template <int BB, int VW, bool DENSE, bool RANDOM>
 __global__ __launch_bounds__(kThreads) void resolve_dots_apply_split(
     RowMap rm, PrevBlock prev, const double *__restrict__ prev_gram, const double *__restrict__ dots_in_part,
     double *__restrict__ dots_out_part, int dot_groups, double *__restrict__ r_sum, int8_t *__restrict__ eps_blk,
-    int8_t *__restrict__ signs_out, double *__restrict__ dots_out, const float *__restrict__ uniforms)
+    int8_t *__restrict__ signs_out, double *__restrict__ dots_out, const float *__restrict__ uniforms,
+    WalkStrides ws)
 {
     __shared__ double part[kSplitGroups][kSplitElems];
     __shared__ double rnew[kSplitElems];
     __shared__ int8_t eps_s[kMaxBlockPairs];
     const int64_t d = rm.d;
+    // blockIdx.y: the walk; what it owns lies at a fixed stride from the first walk's
+    const int64_t w = blockIdx.y;
+    const int64_t woff = w * ws.rows;
+    prev_gram += w * ws.gram;
+    dots_in_part += w * ws.dots;
+    dots_out_part += w * ws.dots;
+    r_sum += w * ws.r;
+    eps_blk += w * kMaxBlockPairs;
+    signs_out += w * ws.out;
+    if (dots_out) dots_out += w * ws.out;
     constexpr int QUADS = kThreads / kSplitGroups;  // 16 threads, four elements each
     const int quad = threadIdx.x % QUADS, grp = threadIdx.x / QUADS;
     const int64_t e = (int64_t)blockIdx.x * kSplitElems + quad * 4;
@@ -771,10 +806,10 @@ __global__ __launch_bounds__(kThreads) void resolve_dots_apply_split(
     for (int q = 0; q < PER; ++q) {
         const int j = grp * PER + q;
         const int jp = j < prev.rm.nb ? j : 0, jc = j < rm.nb ? j : 0;
-        pa[q] = load4_nb<VW>(DENSE ? prev.rm.dense_row(jp, 0) : prev.rm.row(j, 0), true, e, d);
-        pb[q] = load4_nb<VW>(DENSE ? prev.rm.dense_row(jp, 1) : prev.rm.row(j, 1), true, e, d);
-        ca[q] = load4_nb<VW>(DENSE ? rm.dense_row(jc, 0) : rm.row(j, 0), true, e, d);
-        cb[q] = load4_nb<VW>(DENSE ? rm.dense_row(jc, 1) : rm.row(j, 1), true, e, d);
+        pa[q] = load4_nb<VW>((DENSE ? prev.rm.dense_row(jp, 0) : prev.rm.row(j, 0)) + woff, true, e, d);
+        pb[q] = load4_nb<VW>((DENSE ? prev.rm.dense_row(jp, 1) : prev.rm.row(j, 1)) + woff, true, e, d);
+        ca[q] = load4_nb<VW>((DENSE ? rm.dense_row(jc, 0) : rm.row(j, 0)) + woff, true, e, d);
+        cb[q] = load4_nb<VW>((DENSE ? rm.dense_row(jc, 1) : rm.row(j, 1)) + woff, true, e, d);
     }
     if (prev.rm.nb > 0) {  // uniform
         resolve_body<BB, RANDOM, 1, kThreads>(prev_gram, 0, dots_in_part, dot_groups, BB, prev.rm.nb, prev.rm.k0,
@@ -838,12 +873,15 @@ __global__ void fill_zero_f64(double *p, int64_t count) {
 __global__ __launch_bounds__(kMaxBlockPairs) void fill_row_maps(RowMap *__restrict__ maps, const float *base,
                                                                 int64_t m, int64_t n, int64_t d, int bb,
                                                                 int64_t first_pair, int64_t total_pairs,
-                                                                int64_t center_off, int layout)
+                                                                int64_t center_off, int layout,
+                                                                int64_t walk_rows_stride)
 {
     // layout 0: dense [m][n][d];  1: single rows paired with the row at center_off;
     // 2: a staging chunk [q][2][d] that starts at first_pair (base = the chunk)
+    // blockIdx.y: the walk (its rows start walk_rows_stride floats after the previous walk's)
     const int use_center = layout == 1;
-    RowMap &rm = maps[blockIdx.x];
+    base += (int64_t)blockIdx.y * walk_rows_stride;
+    RowMap &rm = maps[(int64_t)blockIdx.y * gridDim.x + blockIdx.x];
     const int j = threadIdx.x;
     const int64_t p0 = first_pair + (int64_t)blockIdx.x * bb;
     const int64_t left = total_pairs - p0;

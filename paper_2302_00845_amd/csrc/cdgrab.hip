@@ -49,9 +49,11 @@ struct cdgrab_handle {
     double *r_sum = nullptr;   int64_t r_cap = 0;         // doubles
     double *partials = nullptr; int64_t partials_cap = 0; // doubles
     double *reduced = nullptr;                            // kReduceSlices x PartLayout<64>::PART doubles
-    int8_t *eps_blk = nullptr;                            // up to 64 signs of the current block
+    int8_t *eps_blk = nullptr; int64_t eps_cap = 0;       // 64 signs of the current block per walk
     int32_t *flag = nullptr;                              // reorder's bad-sign flag
     const float *uniforms = nullptr;                      // caller's draws while a randomized epoch runs
+    int64_t walks = 1;                                    // independent walks per launch while such an epoch runs
+    WalkStrides ws{};                                     // their strides (all zero for one walk)
     float *zero_row = nullptr; int64_t zero_row_cap = 0;  // a zero vector standing in for a missing stale mean
     float *train_delta = nullptr; int64_t train_delta_cap = 0;  // [m][classes] softmax deltas of one step
     int32_t *train_perm = nullptr; int64_t train_perm_cap = 0;  // spare [m][n] order of the multi-epoch driver
@@ -272,14 +274,15 @@ constexpr int64_t kResidentMinD = (int64_t)1 << 21;
 template <int BB, int VW>
 void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
     // short rows: too few flat workgroups to hide latency -> split the pairs over thread groups
-    if (groups < 2 * h->num_cu && h->apply_mode < 3) {
-        const dim3 grid((unsigned)((rm.d + kSplitElems - 1) / kSplitElems));
+    // (several independent walks per launch exist for short rows only, in this form)
+    if ((groups < 2 * h->num_cu && h->apply_mode < 3) || h->walks > 1) {
+        const dim3 grid((unsigned)((rm.d + kSplitElems - 1) / kSplitElems), (unsigned)h->walks);
         if (rm.nb == BB)
             hipLaunchKernelGGL((pass2_apply_split<BB, VW, true>), grid, dim3(kThreads), 0, h->stream, rm,
-                               h->eps_blk, h->r_sum);
+                               h->eps_blk, h->r_sum, h->ws);
         else
             hipLaunchKernelGGL((pass2_apply_split<BB, VW, false>), grid, dim3(kThreads), 0, h->stream, rm,
-                               h->eps_blk, h->r_sum);
+                               h->eps_blk, h->r_sum, h->ws);
         return;
     }
     if (h->apply_mode == 3 || (h->apply_mode != 4 && rm.d >= kResidentMinD)) {
@@ -313,7 +316,7 @@ void launch_resolve(cdgrab_handle *h, const RowMap &rm, int8_t *signs_out, doubl
     auto launch = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, dim3(1), dim3(kResolveThreads<BB>), 0, h->stream, h->reduced,
                            (int64_t)part, h->reduced + PartLayout<BB>::GRAM, kReduceSlices, (int64_t)part, rm.nb,
-                           rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out, h->uniforms);
+                           rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out, dots_out, h->uniforms, WalkStrides{});
     };
     if (h->uniforms) launch(resolve_signs<BB, true, kReduceSlices>);
     else launch(resolve_signs<BB, false, kReduceSlices>);
@@ -329,8 +332,9 @@ int run_block_ahead(cdgrab_handle *h, const RowMap &rm, const PrevBlock &prev, c
     const unsigned groups = (unsigned)((rm.d + kSplitElems - 1) / kSplitElems);
     MARK(h, 2, kPass1);
     auto launch = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, dim3(groups), dim3(kThreads), 0, h->stream, rm, prev, prev_gram, dots_in,
-                           dots_out, (int)groups, h->r_sum, h->eps_blk, signs_out, dots_export, h->uniforms);
+        hipLaunchKernelGGL(kernel, dim3(groups, (unsigned)h->walks), dim3(kThreads), 0, h->stream, rm, prev,
+                           prev_gram, dots_in, dots_out, (int)groups, h->r_sum, h->eps_blk, signs_out, dots_export,
+                           h->uniforms, h->ws);
     };
     auto by_width = [&](auto dense_tag, auto random_tag) {
         constexpr bool DENSE = decltype(dense_tag)::value, RANDOM = decltype(random_tag)::value;
@@ -358,9 +362,9 @@ int run_resolve_ahead(cdgrab_handle *h, const RowMap &rm, const double *gram, co
     const int groups = (int)((rm.d + kSplitElems - 1) / kSplitElems);
     MARK(h, 2, kResolve);
     auto resolve = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, dim3(1), dim3(kResolveThreads<BB>), 0, h->stream, gram, (int64_t)0, dots_in,
-                           groups, (int64_t)BB, rm.nb, rm.k0, rm.i0, rm.m, rm.n / 2, h->eps_blk, signs_out,
-                           dots_export, h->uniforms);
+        hipLaunchKernelGGL(kernel, dim3(1, (unsigned)h->walks), dim3(kResolveThreads<BB>), 0, h->stream, gram,
+                           (int64_t)0, dots_in, groups, (int64_t)BB, rm.nb, rm.k0, rm.i0, rm.m, rm.n / 2,
+                           h->eps_blk, signs_out, dots_export, h->uniforms, h->ws);
     };
     if (h->uniforms) resolve(resolve_signs<BB, true, 1>);
     else resolve(resolve_signs<BB, false, 1>);
@@ -373,26 +377,28 @@ template <int BB>
 int run_grams_ahead(cdgrab_handle *h, int64_t d, const cdgrab_plan &plan, int64_t count, int groups,
                     double *gram_out) {
     constexpr int part = PartLayout<BB>::PART;
-    const dim3 grid((unsigned)groups, (unsigned)count), block(kThreads);
+    const dim3 grid((unsigned)groups, (unsigned)count, (unsigned)h->walks), block(kThreads);
     MARK(h, 2, kPass1);
+    const int64_t ntiles = (d + plan.tile_elems - 1) / plan.tile_elems;
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles, count);
+    };
     if (plan.tile_elems == 128) {
-        const int64_t ntiles = (d + 127) / 128;
         switch (plan.vector_width) {
-            case 4: hipLaunchKernelGGL((gram_batched<BB, 4, 128>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
-            case 2: hipLaunchKernelGGL((gram_batched<BB, 2, 128>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
-            default: hipLaunchKernelGGL((gram_batched<BB, 1, 128>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
+            case 4: launch(gram_batched<BB, 4, 128>); break;
+            case 2: launch(gram_batched<BB, 2, 128>); break;
+            default: launch(gram_batched<BB, 1, 128>); break;
         }
     } else {
-        const int64_t ntiles = (d + 63) / 64;
         switch (plan.vector_width) {
-            case 4: hipLaunchKernelGGL((gram_batched<BB, 4, 64>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
-            case 2: hipLaunchKernelGGL((gram_batched<BB, 2, 64>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
-            default: hipLaunchKernelGGL((gram_batched<BB, 1, 64>), grid, block, 0, h->stream, h->maps, h->r_sum, h->partials, ntiles); break;
+            case 4: launch(gram_batched<BB, 4, 64>); break;
+            case 2: launch(gram_batched<BB, 2, 64>); break;
+            default: launch(gram_batched<BB, 1, 64>); break;
         }
     }
     MARK(h, 2, kReduce);
-    hipLaunchKernelGGL(reduce_batched, dim3((part + kThreads - 1) / kThreads, (unsigned)count), block, 0, h->stream,
-                       h->partials, gram_out, part, groups);
+    hipLaunchKernelGGL(reduce_batched, dim3((part + kThreads - 1) / kThreads, (unsigned)count, (unsigned)h->walks),
+                       block, 0, h->stream, h->partials, gram_out, part, groups, h->ws.gram);
     HIP_TRY(h, hipGetLastError());
     return CDGRAB_OK;
 }
@@ -577,6 +583,7 @@ struct Epoch {
     int gram_groups = 1;       // workgroups per block of the ahead-launch
     int64_t staging_chunk = 0; // floats per staging chunk
     int64_t center_off = 0;    // element offset of center_row from grads
+    int64_t walks = 1;         // independent walks of this shape run side by side (m == 1, dense, Grams ahead)
 
     RowMap rm;
     PrevBlock prev;
@@ -624,32 +631,48 @@ int Epoch::prepare() {
     ahead = plan.gram_ahead != 0;
     batch = streamed ? chunk_pairs / bb : std::min<int64_t>(plan.blocks, kGramBatch);
 
-    // workspace
+    // workspace (per walk when several independent walks run side by side)
+    const int64_t r_pad = round_up(d, kPadE);
+    if (walks > 1 && !(ahead && !streamed && !center_row && m == 1))
+        return fail(h, CDGRAB_EINVAL, "several walks per launch need dense short rows (the Grams-ahead form)");
     int64_t fixed_cap = 0;
-    rc = ensure(h, h->r_sum, h->r_cap, round_up(d, kPadE));
+    rc = ensure(h, h->r_sum, h->r_cap, walks * r_pad);
     if (rc) return rc;
     rc = ensure(h, h->partials, h->partials_cap, (int64_t)plan.pass1_groups * part_size(bb));
     if (rc) return rc;
     if (!h->reduced) { fixed_cap = 0; rc = ensure(h, h->reduced, fixed_cap, (int64_t)kReduceSlices * PartLayout<64>::PART); if (rc) return rc; }
-    if (!h->eps_blk) { fixed_cap = 0; rc = ensure(h, h->eps_blk, fixed_cap, (int64_t)64); if (rc) return rc; }
+    rc = ensure(h, h->eps_blk, h->eps_cap, walks * kMaxBlockPairs);
+    if (rc) return rc;
     if (streamed) {
         // two chunks when a launch reads the previous block's rows as well: they must outlive the next fill
         rc = ensure(h, h->staging, h->staging_cap, ((fused || ahead) ? 2 : 1) * staging_chunk);
         if (rc) return rc;
     }
+    h->ws = WalkStrides{};
     if (ahead) {
         // enough workgroups to fill the chip, at least one tile each
         const int64_t ntiles = (d + plan.tile_elems - 1) / plan.tile_elems;
-        gram_groups = (int)std::max<int64_t>(1, std::min<int64_t>(ntiles, (4 * h->num_cu + batch - 1) / batch));
-        rc = ensure(h, h->partials, h->partials_cap, batch * gram_groups * part_size(bb));
+        const int64_t launches = batch * walks;
+        gram_groups = (int)std::max<int64_t>(1, std::min<int64_t>(ntiles, (4 * h->num_cu + launches - 1) / launches));
+        const int64_t dot_len = (d + kSplitElems - 1) / kSplitElems * bb;
+        rc = ensure(h, h->partials, h->partials_cap, walks * batch * gram_groups * part_size(bb));
         if (rc) return rc;
-        rc = ensure(h, h->gram_all, h->gram_all_cap, (batch + 1) * part_size(bb));
+        rc = ensure(h, h->gram_all, h->gram_all_cap, walks * (batch + 1) * part_size(bb));
         if (rc) return rc;
-        rc = ensure(h, h->dot_partials, h->dot_partials_cap, 2 * ((d + kSplitElems - 1) / kSplitElems * bb));
+        rc = ensure(h, h->dot_partials, h->dot_partials_cap, walks * 2 * dot_len);
         if (rc) return rc;
-        rc = ensure(h, h->maps, h->maps_cap, batch);
+        rc = ensure(h, h->maps, h->maps_cap, walks * batch);
         if (rc) return rc;
+        if (walks > 1) {
+            h->ws.rows = n * d;
+            h->ws.r = r_pad;
+            h->ws.gram = (batch + 1) * part_size(bb);
+            h->ws.dots = 2 * dot_len;
+            h->ws.out = n / 2;
+            h->ws.maps = batch;
+        }
     }
+    h->walks = walks;
 
     center_off = center_row ? (int64_t)((reinterpret_cast<intptr_t>(center_row) - reinterpret_cast<intptr_t>(grads)) /
                                         (intptr_t)sizeof(float))
@@ -714,11 +737,12 @@ int Epoch::chain_ahead() {
         if (streamed && (rc = generate(first, cnt_pairs, stage_buf))) return rc;
         MARK(h, 1, kBalance);
         if (b0 > 0)
-            HIP_TRY(h, hipMemcpyAsync(h->gram_all, h->gram_all + prev_slot * part, (size_t)part * sizeof(double),
-                                      hipMemcpyDeviceToDevice, h->stream));
-        hipLaunchKernelGGL(fill_row_maps, dim3((unsigned)count), dim3(kMaxBlockPairs), 0, h->stream, h->maps,
-                           streamed ? stage_buf : grads, m, n, d, bb, first, plan.pairs, center_off,
-                           streamed ? 2 : (center_row ? 1 : 0));
+            for (int64_t w = 0; w < walks; ++w)
+                HIP_TRY(h, hipMemcpyAsync(h->gram_all + w * h->ws.gram, h->gram_all + w * h->ws.gram + prev_slot * part,
+                                          (size_t)part * sizeof(double), hipMemcpyDeviceToDevice, h->stream));
+        hipLaunchKernelGGL(fill_row_maps, dim3((unsigned)count, (unsigned)walks), dim3(kMaxBlockPairs), 0, h->stream,
+                           h->maps, streamed ? stage_buf : grads, m, n, d, bb, first, plan.pairs, center_off,
+                           streamed ? 2 : (center_row ? 1 : 0), h->ws.rows);
         double *gram_out = h->gram_all + part;
         rc = BY_BLOCK_PAIRS(bb, run_grams_ahead<64>(h, d, plan, count, gram_groups, gram_out),
                             run_grams_ahead<32>(h, d, plan, count, gram_groups, gram_out),
@@ -795,15 +819,16 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
                               cdgrab_gen_fn gen, void *gen_ctx, int64_t chunk_pairs,
                               const int32_t *perm_in, int8_t *signs_out, int32_t *perm_out,
                               float *r_out, double *r64_out, double *dots_out,
-                              const float *center_row = nullptr) {
+                              const float *center_row = nullptr, int64_t walks = 1) {
     if (!h) return CDGRAB_EINVAL;
     if (!signs_out || (!perm_out && !center_row))
         return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: signs_out and perm_out are required");
     Epoch ep{h, m, n, d, grads, gen, gen_ctx, chunk_pairs, center_row, signs_out, dots_out};
+    ep.walks = walks;
     int rc = ep.prepare();
     if (rc) return rc;
     // the permutation kernel reads perm_in while other threads write perm_out
-    if (ranges_overlap(perm_in, m * n * 4, perm_out, m * n * 4))
+    if (ranges_overlap(perm_in, walks * m * n * 4, perm_out, walks * m * n * 4))
         return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch: perm_in and perm_out must not overlap");
 
     h->marks.clear();
@@ -817,9 +842,9 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     if (rc) return rc;
 
     MARK(h, 1, kFinish);
-    if (!center_row)
-        hipLaunchKernelGGL(build_pair_permutations, dim3((unsigned)((m * (n / 2) + 255) / 256)), dim3(256), 0,
-                           h->stream, signs_out, perm_in, perm_out, m, n);
+    if (!center_row)  // (side-by-side walks are one-worker walks: `walks` rows of signs and orders)
+        hipLaunchKernelGGL(build_pair_permutations, dim3((unsigned)((walks * m * (n / 2) + 255) / 256)), dim3(256),
+                           0, h->stream, signs_out, perm_in, perm_out, walks * m, n);
     if (r_out || r64_out)
         hipLaunchKernelGGL(export_running_sum, dim3((unsigned)std::min<int64_t>(8192, (d + 255) / 256)), dim3(256),
                            0, h->stream, h->r_sum, d, r_out, r64_out);
@@ -832,6 +857,8 @@ static int balance_epoch_impl(cdgrab_handle *h, int64_t m, int64_t n, int64_t d,
     h->last.block_pairs = (int32_t)bb;
     h->last.pass1_groups = ep.plan.pass1_groups;
     h->have_timing = h->timing >= 1;
+    h->walks = 1;
+    h->ws = WalkStrides{};
     return CDGRAB_OK;
 }
 
@@ -903,8 +930,8 @@ int cdgrab_balance_epoch_static(cdgrab_handle *h, int64_t m, int64_t n, int64_t 
     // form, no timing events, at most kStaticGroups workgroups in the dot/Gram pass.
     struct Saved {
         double *r_sum, *partials, *reduced; int8_t *eps_blk;
-        int64_t r_cap, partials_cap; int timing, gram_mode, pass1_groups_opt; bool fixed;
-    } sv{h->r_sum, h->partials, h->reduced, h->eps_blk, h->r_cap, h->partials_cap,
+        int64_t r_cap, partials_cap, eps_cap; int timing, gram_mode, pass1_groups_opt; bool fixed;
+    } sv{h->r_sum, h->partials, h->reduced, h->eps_blk, h->r_cap, h->partials_cap, h->eps_cap,
          h->timing, h->gram_mode, h->pass1_groups_opt, h->fixed_workspace};
     h->r_sum = base;
     h->r_cap = d > 0 ? round_up(d, kPadE) : 0;  // only this much is cleared and used
@@ -912,6 +939,7 @@ int cdgrab_balance_epoch_static(cdgrab_handle *h, int64_t m, int64_t n, int64_t 
     h->partials_cap = kStaticPartials;
     h->reduced = h->partials + kStaticPartials;
     h->eps_blk = reinterpret_cast<int8_t *>(h->reduced + kStaticReduced);
+    h->eps_cap = kMaxBlockPairs;
     h->fixed_workspace = true;
     h->timing = 0;
     h->gram_mode = 1;
@@ -920,7 +948,7 @@ int cdgrab_balance_epoch_static(cdgrab_handle *h, int64_t m, int64_t n, int64_t 
     rc = balance_epoch_impl(h, m, n, d, grads, nullptr, nullptr, 0, perm_in, signs_out, perm_out, r_out,
                             r64_out, dots_out);
     h->r_sum = sv.r_sum; h->partials = sv.partials; h->reduced = sv.reduced; h->eps_blk = sv.eps_blk;
-    h->r_cap = sv.r_cap; h->partials_cap = sv.partials_cap;
+    h->r_cap = sv.r_cap; h->partials_cap = sv.partials_cap; h->eps_cap = sv.eps_cap;
     h->timing = sv.timing; h->gram_mode = sv.gram_mode; h->pass1_groups_opt = sv.pass1_groups_opt;
     h->fixed_workspace = sv.fixed;
     h->have_timing = false;
@@ -986,7 +1014,23 @@ int cdgrab_balance_epoch_independent(cdgrab_handle *h, int64_t m, int64_t n, int
     if (m < 1) return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_independent: need m>=1");
     if (!grads || !signs_out || !perm_out)
         return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_independent: null pointer");
-    // m separate one-worker walks: worker i balances its own n/2 pairs on its own running sum
+    if (n < 2 || (n & 1) || d < 1 || m > (INT64_MAX / n) / d)
+        return fail(h, CDGRAB_EINVAL, "cdgrab_balance_epoch_independent: need even n >= 2, d >= 1");
+    // Short rows (the Grams-ahead form): the m one-worker walks run side by side, the worker
+    // as a grid coordinate, each on its own running sum -- every launch of the chain serves all
+    // workers.  Same kernels, same sums in the same order as a one-worker epoch.  (A worker's
+    // rows start n*d floats after the previous worker's: as aligned as the first worker's
+    // whenever d suits the load width.)
+    if (m > 1 && m <= 65535) {
+        const uintptr_t a = reinterpret_cast<uintptr_t>(grads);
+        cdgrab_plan one{};
+        const int prc = plan_epoch(1, n, d, h->block_pairs_opt, 0, (a % 16 == 0) ? 16 : (a % 8 == 0) ? 8 : 4,
+                                   h->num_cu, h->pass1_groups_opt, h->apply_mode, h->gram_mode, 0, &one);
+        if (prc == CDGRAB_OK && one.gram_ahead)
+            return balance_epoch_impl(h, 1, n, d, grads, nullptr, nullptr, 0, perm_in, signs_out, perm_out,
+                                      nullptr, nullptr, nullptr, nullptr, m);
+    }
+    // long rows: m separate one-worker epochs, each bound by bytes, not by launches
     for (int64_t i = 0; i < m; ++i) {
         int rc = balance_epoch_impl(h, 1, n, d, grads + i * n * d, nullptr, nullptr, 0,
                                     perm_in ? perm_in + i * n : nullptr, signs_out + i * (n / 2),
@@ -1125,21 +1169,26 @@ int cdgrab_herding_bound(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
     HIP_TRY(h, hipSetDevice(h->device));
     HerdingShape sh;
     sh.m = m; sh.n = n; sh.d = d;
-    // enough (segment, element) threads to fill the chip, at least one step per segment
+    // enough (segment, four elements) threads to fill the chip, at least one step per segment
     const int64_t quads = (d + 3) / 4;
+    sh.quads = (int32_t)std::min<int64_t>(quads, INT32_MAX);
+    // short rows: a workgroup serves several segments (thread = (segment, four elements))
+    sh.spw = quads <= 128 ? (int32_t)(256 / quads) : 1;
     int64_t want_threads = (int64_t)h->num_cu * 2048;
-    // a workgroup serves one segment: blockIdx.y (at most 65 535 of them)
-    int64_t segs = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(n, 65535), (want_threads + quads - 1) / quads));
+    // blockIdx.y counts workgroups of spw segments (at most 65 535 of them)
+    int64_t segs = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(n, (int64_t)65535 * sh.spw),
+                                                          (want_threads + quads - 1) / quads));
     sh.seg_len = (n + segs - 1) / segs;
     sh.segments = (n + sh.seg_len - 1) / sh.seg_len;
     int rc = ensure(h, h->herd_ws, h->herd_cap, 2 * sh.segments * d + d);
     if (rc) return rc;
     double *segsum = h->herd_ws, *start = segsum + sh.segments * d, *zbar = start + sh.segments * d;
-    const dim3 grid((unsigned)((quads + 255) / 256), (unsigned)sh.segments);
+    const dim3 grid(sh.spw == 1 ? (unsigned)((quads + 255) / 256) : 1u,
+                    (unsigned)((sh.segments + sh.spw - 1) / sh.spw));
     unsigned long long *bits = reinterpret_cast<unsigned long long *>(bound_out);
     // the segment's example ids go through LDS when they fit (48 KB)
     const size_t ids_bytes = (size_t)(sh.seg_len * m) * sizeof(int32_t);
-    const int lds_ids = (perm && ids_bytes <= 48 * 1024) ? 1 : 0;
+    const int lds_ids = (perm && sh.spw == 1 && ids_bytes <= 48 * 1024) ? 1 : 0;
     const size_t lds = lds_ids ? ids_bytes : 0;
     // widest load every row start allows
     const uintptr_t zb = reinterpret_cast<uintptr_t>(z);
@@ -1148,8 +1197,14 @@ int cdgrab_herding_bound(cdgrab_handle *h, int64_t m, int64_t n, int64_t d, cons
     auto launch = [&](auto vw_tag) {
         constexpr int VW = decltype(vw_tag)::value;
         hipLaunchKernelGGL((herding_segment_sums<VW>), grid, dim3(256), lds, h->stream, z, perm, sh, lds_ids, segsum);
-        hipLaunchKernelGGL(herding_segment_offsets, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, h->stream,
-                           segsum, sh, zbar, start);
+        // the prefix over segments: one thread per element for long rows, a workgroup scan per
+        // element for short ones (many segments, few elements)
+        if (sh.spw == 1)
+            hipLaunchKernelGGL(herding_segment_offsets, dim3((unsigned)((d + 255) / 256)), dim3(256), 0, h->stream,
+                               segsum, sh, zbar, start);
+        else
+            hipLaunchKernelGGL(herding_segment_offsets_scan, dim3((unsigned)d), dim3(256), 0, h->stream,
+                               segsum, sh, zbar, start);
         hipLaunchKernelGGL((herding_prefix_max<VW>), grid, dim3(256), lds, h->stream, z, perm, sh, lds_ids, zbar,
                            start, bits);
     };

@@ -18,7 +18,24 @@ struct HerdingShape {
     int64_t m, n, d;
     int64_t segments;  // number of step segments
     int64_t seg_len;   // steps per segment (last one may be shorter)
+    int32_t spw;       // segments per workgroup: 1 for long rows (a workgroup spans 1024 elements of
+                       // one segment); 256 / quads for short rows (thread = (segment, four elements)),
+                       // so that a 64-byte row still keeps every lane busy
+    int32_t quads;     // ceil(d / 4)
 };
+
+// Which (segment, group of four elements) a thread serves.  Returns false for an idle thread.
+__device__ __forceinline__ bool herding_thread_role(const HerdingShape &sh, int64_t &s, int64_t &qd) {
+    if (sh.spw == 1) {
+        s = blockIdx.y;
+        qd = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        return qd < sh.quads;
+    }
+    const int sl = (int)threadIdx.x / sh.quads;
+    qd = (int)threadIdx.x - sl * sh.quads;
+    s = (int64_t)blockIdx.y * sh.spw + sl;
+    return sl < sh.spw && s < sh.segments;
+}
 
 // Sum over the workers of elements e .. e+3 of step j's vectors.  VW = widest
 // aligned load every row start allows (as in the balancing kernels).  ids: the m
@@ -54,8 +71,6 @@ __device__ __forceinline__ const int32_t *herding_stage_ids(const int32_t *__res
     return ids_lds;
 }
 
-__device__ __forceinline__ int64_t herding_quads(const HerdingShape &sh) { return (sh.d + 3) / 4; }
-
 // Pass A: segsum[s][e] = sum over the segment's steps and all workers.  One thread
 // per (segment = blockIdx.y, four consecutive elements).
 template <int VW>
@@ -64,13 +79,13 @@ __global__ __launch_bounds__(256) void herding_segment_sums(const float *__restr
                                                             int lds_ids, double *__restrict__ segsum)
 {
     extern __shared__ int32_t ids_lds[];
-    const int64_t quads = herding_quads(sh);
-    const int64_t s = blockIdx.y;
+    int64_t s, qd;
+    const bool active = herding_thread_role(sh, s, qd);
     const int64_t j0 = s * sh.seg_len;
     const int64_t j1 = (j0 + sh.seg_len < sh.n) ? j0 + sh.seg_len : sh.n;
-    const int32_t *ids = herding_stage_ids(perm, sh, j0, j1, lds_ids, ids_lds);
-    const int64_t qd = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (qd >= quads) return;
+    // (ids are staged per workgroup, i.e. only when a workgroup serves one segment)
+    const int32_t *ids = herding_stage_ids(perm, sh, j0, j1, sh.spw == 1 ? lds_ids : 0, ids_lds);
+    if (!active) return;
     const int64_t e = qd * 4;
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     for (int64_t j = j0; j < j1; ++j) {
@@ -107,6 +122,46 @@ __global__ __launch_bounds__(256) void herding_segment_offsets(const double *__r
     }
 }
 
+// Pass B for short rows, where there are many segments and few elements: one workgroup per
+// element; thread t takes a run of consecutive segments, the workgroup adds the runs' sums
+// (mean), scans the centred run sums in thread order, and every thread then walks its run.
+__global__ __launch_bounds__(256) void herding_segment_offsets_scan(const double *__restrict__ segsum,
+                                                                    HerdingShape sh, double *__restrict__ zbar,
+                                                                    double *__restrict__ start)
+{
+    __shared__ double part[256];
+    const int64_t e = blockIdx.x;
+    const int64_t run_len = (sh.segments + 255) / 256;
+    const int64_t s0 = (int64_t)threadIdx.x * run_len;
+    const int64_t s1 = (s0 + run_len < sh.segments) ? s0 + run_len : sh.segments;
+    double local = 0.0;
+    for (int64_t s = s0; s < s1; ++s) local += segsum[s * sh.d + e];
+    part[threadIdx.x] = local;
+    __syncthreads();
+    double total = 0.0;
+    for (int q = 0; q < 256; ++q) total += part[q];
+    const double mean = total / (double)(sh.m * sh.n);
+    __syncthreads();
+    // steps covered by this thread's run (the last segment may be shorter)
+    int64_t steps = 0;
+    if (s0 < s1) {
+        const int64_t j_first = s0 * sh.seg_len;
+        const int64_t j_end = (s1 * sh.seg_len < sh.n) ? s1 * sh.seg_len : sh.n;
+        steps = j_end - j_first;
+    }
+    part[threadIdx.x] = local - (double)(steps * sh.m) * mean;
+    __syncthreads();
+    double run = 0.0;
+    for (int q = 0; q < (int)threadIdx.x; ++q) run += part[q];
+    for (int64_t s = s0; s < s1; ++s) {
+        start[s * sh.d + e] = run;
+        const int64_t j0 = s * sh.seg_len;
+        const int64_t len = ((j0 + sh.seg_len < sh.n) ? sh.seg_len : sh.n - j0);
+        run += segsum[s * sh.d + e] - (double)(len * sh.m) * mean;
+    }
+    if (threadIdx.x == 0) zbar[e] = mean;
+}
+
 // Pass C: replay each segment from its starting prefix; the largest |prefix| seen
 // anywhere is folded into *bound with an integer max on the bit pattern (valid
 // for non-negative doubles).
@@ -119,14 +174,13 @@ __global__ __launch_bounds__(256) void herding_prefix_max(const float *__restric
 {
     __shared__ double wave_max[4];
     extern __shared__ int32_t ids_lds[];
-    const int64_t quads = herding_quads(sh);
-    const int64_t s = blockIdx.y;
+    int64_t s, qd;
+    const bool active = herding_thread_role(sh, s, qd);
     const int64_t j0 = s * sh.seg_len;
     const int64_t j1 = (j0 + sh.seg_len < sh.n) ? j0 + sh.seg_len : sh.n;
-    const int32_t *ids = herding_stage_ids(perm, sh, j0, j1, lds_ids, ids_lds);
-    const int64_t qd = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int32_t *ids = herding_stage_ids(perm, sh, j0, j1, sh.spw == 1 ? lds_ids : 0, ids_lds);
     double mx = 0.0;
-    if (qd < quads) {
+    if (active) {
         const int64_t e = qd * 4;
         double centre[4], acc[4];
 #pragma unroll

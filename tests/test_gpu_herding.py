@@ -34,7 +34,8 @@ def test_closed_form_cases(lib):
 
 
 @pytest.mark.parametrize("m,n,d", [(1, 1, 1), (3, 7, 5), (4, 64, 1024), (5, 400, 16), (16, 50, 7850),
-                                   (2, 3000, 3), (8, 33, 300)])
+                                   (2, 3000, 3), (8, 33, 300), (5, 20000, 16), (100, 1000, 16), (3, 70001, 8),
+                                   (2, 999, 512), (7, 130, 516), (1, 300000, 1)])
 @pytest.mark.parametrize("with_perm", [False, True])
 def test_matches_oracle(lib, m, n, d, with_perm):
     h = lib.Handle()
@@ -45,17 +46,35 @@ def test_matches_oracle(lib, m, n, d, with_perm):
     assert abs(got - want) <= 1e-9 * max(want, 1e-30)
 
 
-def test_independent_walks_match_oracle(lib):
-    """ID-GraB (PairBal): worker i's signs and order are those of a one-worker walk."""
-    m, n, d = 5, 24, 300
-    z = workloads.heavy_rows(9, m, n, d)
+@pytest.mark.parametrize("m,n,d,exact", [
+    (5, 24, 300, False),        # one block per worker: m one-worker epochs back to back
+    (7, 200, 300, False),       # two blocks: the walks run side by side, the worker as a grid coordinate
+    (3, 2100, 40, True),        # seventeen blocks, a ragged last one, exact ties
+    (4, 300, 1001, True),       # odd row length: scalar loads, rows of later workers unaligned
+    (16, 468, 7850, False),     # config 2's row length
+    (2, 66000, 8, True),        # 516 blocks: more than one batch of Gram matrices, the last tile carried over
+    (70, 130, 16, False)])
+def test_independent_walks_match_oracle(lib, m, n, d, exact):
+    """ID-GraB (PairBal): worker i's signs and order are those of a one-worker walk over its
+    own rows, whether the library runs the m walks one after the other or side by side."""
+    from parity import judge_greedy, replay_pairs, flatten_pairs, expected_perm_from_signs
+    z = workloads.integer_rows(9, m, n, d, 4) if exact else workloads.heavy_rows(9, m, n, d)
     perm_in = workloads.random_perms(4, m, n)
     h = lib.Handle()
     out = lib.cdgrab_balance_epoch_independent(h, torch.from_numpy(z).cuda(), torch.from_numpy(perm_in).cuda())
     signs, perm = out["signs"].cpu().numpy(), out["perm"].cpu().numpy()
     for i in range(m):
         ref = oracle.server_epoch(z[i:i + 1], perm_in[i:i + 1])
-        assert np.array_equal(ref["eps"][0], signs[i]) and np.array_equal(ref["perm"][0], perm[i])
+        if not np.array_equal(ref["eps"][0], signs[i]):
+            assert not exact
+            # a near-tie decided the other way: judge worker i's walk by replay
+            _, t, nr, nc = replay_pairs(flatten_pairs(z[i:i + 1]), signs[i])
+            judge_greedy(t, nr, nc, signs[i])
+    assert np.array_equal(perm, expected_perm_from_signs(signs, perm_in))
+    # a coordinated epoch on the same handle afterwards is unaffected
+    g = lib.cdgrab_balance_epoch(h, m, n, d, grads=torch.from_numpy(z).cuda(), want_r64=True, want_dots=True)
+    from parity import check_epoch
+    check_epoch(z, {k: (v.cpu().numpy() if v is not None else None) for k, v in g.items()})
 
 
 def _run_orders(lib, h, z, epochs, coordinated):
@@ -177,3 +196,65 @@ def test_stale_mean_balance_matches_oracle(lib, n, d, exact):
     ref0 = oracle.grab_stale_mean(g)
     if exact:
         assert np.array_equal(out0["signs"].cpu().numpy(), ref0["s"])
+
+
+def _run_stale_mean_orders(lib, h, z, epochs):
+    """ID-GraB (Bal): every worker balances its own vectors, centred by the mean of its
+    previous epoch (zero before the first), with no shared state."""
+    m, n, d = z.shape
+    perm = torch.arange(n, dtype=torch.int32, device="cuda").repeat(m, 1).contiguous()
+    stale = [None] * m
+    for _ in range(epochs):
+        idx = perm.long().unsqueeze(-1).expand(m, n, d)
+        visited = torch.gather(z, 1, idx).contiguous()
+        nxt = torch.empty_like(perm)
+        for i in range(m):
+            out = lib.cdgrab_balance_epoch_stale_mean(h, visited[i], stale[i], perm[i].contiguous())
+            nxt[i] = out["perm"]
+            stale[i] = out["mean"]
+        perm = nxt
+    return perm
+
+
+@pytest.mark.timeout(900)
+def test_synthetic_herding_study_at_paper_scale(lib):
+    """App. E's synthetic study as the paper states it: one million vectors from Unif(0,1)^16,
+    zero-centred and scaled to unit length, split evenly over m = 5, 10, 20, 50, 100 workers,
+    three seeds; orders from CD-GraB (coordinated pair balancing), ID-GraB (PairBal)
+    (independent pair balancing), ID-GraB (Bal) (independent balancing with a stale mean) and
+    random orders (D-RR), compared on the parallel herding objective.  The paper reports a
+    figure, so only its qualitative content can be checked: coordinated balancing is lowest
+    and flat in m, the uncoordinated variants grow with m."""
+    h = lib.Handle()
+    N, d, epochs = 1_000_000, 16, 8
+    ms = (5, 10, 20, 50, 100)
+    table = {}
+    for seed in range(3):
+        vec = workloads.herding_vectors(100 + seed, N, d)
+        coord, pair, bal, rand = [], [], [], []
+        for m in ms:
+            n = N // m
+            z = torch.from_numpy(vec.reshape(m, n, d)).cuda()
+            perm_c = _run_orders(lib, h, z, epochs, True)
+            coord.append(gpu_bound(lib, h, z, perm_c))
+            pair.append(gpu_bound(lib, h, z, _run_orders(lib, h, z, epochs, False)))
+            # the stale-mean variant costs a call per worker and epoch: fewer epochs, first seed only
+            if seed == 0:
+                bal.append(gpu_bound(lib, h, z, _run_stale_mean_orders(lib, h, z, 4)))
+            rand.append(gpu_bound(lib, h, z, workloads.random_perms(seed * 1000 + m, m, n)))
+            if seed == 0:
+                # the evaluator itself, at this size, against the oracle
+                want = oracle.parallel_herding(vec.reshape(m, n, d), perm_c.cpu().numpy())
+                assert abs(coord[-1] - want) <= 1e-9 * want
+            del z
+        table[seed] = (coord, pair, bal, rand)
+        print("seed %d  CD-GraB %s | ID-GraB (PairBal) %s | ID-GraB (Bal) %s | random %s" % (
+            seed, ["%.2f" % b for b in coord], ["%.2f" % b for b in pair], ["%.2f" % b for b in bal],
+            ["%.0f" % b for b in rand]))
+        assert max(coord) < 2.0 * min(coord)                          # flat in m
+        assert all(c < p for c, p in zip(coord, pair))                # lowest
+        assert coord[-1] < 0.5 * pair[-1]
+        assert pair[-1] > 2.0 * pair[0] and pair[2] > pair[0]         # uncoordinated: grows with m
+        assert all(c < 0.2 * r for c, r in zip(coord, rand))
+        if bal:
+            assert all(c < b for c, b in zip(coord, bal)) and bal[-1] > bal[0]
