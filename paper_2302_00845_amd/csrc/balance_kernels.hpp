@@ -652,56 +652,58 @@ __global__ __launch_bounds__(kThreads) void pass2_apply(RowMap rm, const int8_t 
 // all), streams all rows of the block for one group after the other and keeps the sums in
 // registers; only when all its groups are done does it read, update and write the running
 // sum.  All workgroups run in step, so the launch is a long stretch of pure row reads
-// followed by one short burst of running-sum reads and writes (per slab, when the row is
-// longer than the registers of the chip hold: kuse * T * 4 elements per slab).
+// followed by one short burst of running-sum reads and writes.  A row longer than the
+// registers of the chip hold (kuse * T * 4 elements) is cut into slabs, ONE LAUNCH PER SLAB:
+// the launch boundary brings the workgroups back into step -- inside one launch they drift
+// apart from slab to slab, the bursts smear out into the row reads, and the gain is lost
+// (d = 124M, eleven slabs: 6.06 ms in one launch, the same as the flat form).
 // Writes scattered through a read stream cost this chip about 1 us per MB (the flat form
 // above: 0.52 ms per 32-pair block at d = 11.2M, of which 0.09 ms for 180 MB of running-sum
-// traffic); gathered at the end they cost a third of that (0.475 ms).  Same sums in the
+// traffic); gathered at the end they cost a third of that (0.46 ms).  Same sums in the
 // same order as the flat form: bit-identical results.
 constexpr int kResidentGroups = 22;
 
 template <int BB, int VW, bool FULL>
 __global__ __launch_bounds__(kThreads, 2) void pass2_apply_resident(RowMap rm, const int8_t *__restrict__ eps_blk,
-                                                                    double *__restrict__ r_sum, int kuse, int slabs)
+                                                                    double *__restrict__ r_sum, int kuse,
+                                                                    int64_t g0)
 {
+    // this launch: groups g0 .. g0 + kuse - 1 of every thread (one slab)
     constexpr int K = kResidentGroups;
     const int64_t d = rm.d;
     const int64_t T = (int64_t)gridDim.x * kThreads;
     const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    for (int s = 0; s < slabs; ++s) {
-        double acc[K][4];
-        const int64_t g0 = (int64_t)s * kuse;
+    double acc[K][4];
 #pragma unroll
-        for (int g = 0; g < K; ++g) {
-            acc[g][0] = acc[g][1] = acc[g][2] = acc[g][3] = 0.0;
-            const int64_t e = ((g0 + g) * T + t) * 4;
-            if (g < kuse && e < d) {
+    for (int g = 0; g < K; ++g) {
+        acc[g][0] = acc[g][1] = acc[g][2] = acc[g][3] = 0.0;
+        const int64_t e = ((g0 + g) * T + t) * 4;
+        if (g < kuse && e < d) {
 #pragma unroll 2
-                for (int j = 0; j < BB; ++j) {
-                    if (FULL || j < rm.nb) {
-                        float4 a = load4<VW>(rm.row(j, 0), e, d);
-                        float4 b = load4<VW>(rm.row(j, 1), e, d);
-                        double sg = (double)eps_blk[j];
-                        acc[g][0] = __builtin_fma(sg, (double)b.x - (double)a.x, acc[g][0]);
-                        acc[g][1] = __builtin_fma(sg, (double)b.y - (double)a.y, acc[g][1]);
-                        acc[g][2] = __builtin_fma(sg, (double)b.z - (double)a.z, acc[g][2]);
-                        acc[g][3] = __builtin_fma(sg, (double)b.w - (double)a.w, acc[g][3]);
-                    }
+            for (int j = 0; j < BB; ++j) {
+                if (FULL || j < rm.nb) {
+                    float4 a = load4<VW>(rm.row(j, 0), e, d);
+                    float4 b = load4<VW>(rm.row(j, 1), e, d);
+                    double sg = (double)eps_blk[j];
+                    acc[g][0] = __builtin_fma(sg, (double)b.x - (double)a.x, acc[g][0]);
+                    acc[g][1] = __builtin_fma(sg, (double)b.y - (double)a.y, acc[g][1]);
+                    acc[g][2] = __builtin_fma(sg, (double)b.z - (double)a.z, acc[g][2]);
+                    acc[g][3] = __builtin_fma(sg, (double)b.w - (double)a.w, acc[g][3]);
                 }
             }
         }
-        // the running sum is padded to a multiple of the tile; the padding stays zero
-        // because elements beyond d load as zero
+    }
+    // the running sum is padded to a multiple of the tile; the padding stays zero
+    // because elements beyond d load as zero
 #pragma unroll
-        for (int g = 0; g < K; ++g) {
-            const int64_t e = ((g0 + g) * T + t) * 4;
-            if (g < kuse && e < d) {
-                double2 lo = *reinterpret_cast<double2 *>(r_sum + e);
-                double2 hi = *reinterpret_cast<double2 *>(r_sum + e + 2);
-                lo.x += acc[g][0]; lo.y += acc[g][1]; hi.x += acc[g][2]; hi.y += acc[g][3];
-                *reinterpret_cast<double2 *>(r_sum + e) = lo;
-                *reinterpret_cast<double2 *>(r_sum + e + 2) = hi;
-            }
+    for (int g = 0; g < K; ++g) {
+        const int64_t e = ((g0 + g) * T + t) * 4;
+        if (g < kuse && e < d) {
+            double2 lo = *reinterpret_cast<double2 *>(r_sum + e);
+            double2 hi = *reinterpret_cast<double2 *>(r_sum + e + 2);
+            lo.x += acc[g][0]; lo.y += acc[g][1]; hi.x += acc[g][2]; hi.y += acc[g][3];
+            *reinterpret_cast<double2 *>(r_sum + e) = lo;
+            *reinterpret_cast<double2 *>(r_sum + e + 2) = hi;
         }
     }
 }

@@ -249,22 +249,16 @@ void launch_pass1(cdgrab_handle *h, const RowMap &rm, const PrevBlock *prev, con
     none.rm.nb = 0;
     none.eps = h->eps_blk;
     const dim3 grid(plan.pass1_groups), block(kThreads);
+    const int64_t ntiles = (rm.d + plan.tile_elems - 1) / plan.tile_elems;
+    auto launch = [&](auto kernel, const PrevBlock &pb) {
+        hipLaunchKernelGGL(kernel, grid, block, 0, h->stream, rm, pb, h->r_sum, h->partials, ntiles);
+    };
     if (plan.tile_elems == 128) {
-        int64_t ntiles = (rm.d + 127) / 128;
-        if (prev)
-            hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 128, true>), grid, block, 0, h->stream, rm, *prev,
-                               h->r_sum, h->partials, ntiles);
-        else
-            hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 128, false>), grid, block, 0, h->stream, rm, none,
-                               h->r_sum, h->partials, ntiles);
+        if (prev) launch(pass1_dots_gram<BB, VW, 128, true>, *prev);
+        else launch(pass1_dots_gram<BB, VW, 128, false>, none);
     } else {
-        int64_t ntiles = (rm.d + 63) / 64;
-        if (prev)
-            hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 64, true>), grid, block, 0, h->stream, rm, *prev,
-                               h->r_sum, h->partials, ntiles);
-        else
-            hipLaunchKernelGGL((pass1_dots_gram<BB, VW, 64, false>), grid, block, 0, h->stream, rm, none,
-                               h->r_sum, h->partials, ntiles);
+        if (prev) launch(pass1_dots_gram<BB, VW, 64, true>, *prev);
+        else launch(pass1_dots_gram<BB, VW, 64, false>, none);
     }
 }
 // Rows from this length on take the resident form of the apply pass (the running-sum
@@ -294,12 +288,16 @@ void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
         const int64_t per_thread = (quads + T - 1) / T;
         const int64_t slabs = (per_thread + kResidentGroups - 1) / kResidentGroups;
         const int kuse = (int)((per_thread + slabs - 1) / slabs);
-        if (rm.nb == BB)
-            hipLaunchKernelGGL((pass2_apply_resident<BB, VW, true>), dim3((unsigned)grid), dim3(kThreads), 0,
-                               h->stream, rm, h->eps_blk, h->r_sum, kuse, (int)slabs);
-        else
-            hipLaunchKernelGGL((pass2_apply_resident<BB, VW, false>), dim3((unsigned)grid), dim3(kThreads), 0,
-                               h->stream, rm, h->eps_blk, h->r_sum, kuse, (int)slabs);
+        // one launch per slab: the boundary keeps the workgroups in step, so that each slab ends in
+        // one burst of running-sum traffic
+        for (int64_t sl = 0; sl < slabs; ++sl) {
+            if (rm.nb == BB)
+                hipLaunchKernelGGL((pass2_apply_resident<BB, VW, true>), dim3((unsigned)grid), dim3(kThreads), 0,
+                                   h->stream, rm, h->eps_blk, h->r_sum, kuse, sl * kuse);
+            else
+                hipLaunchKernelGGL((pass2_apply_resident<BB, VW, false>), dim3((unsigned)grid), dim3(kThreads), 0,
+                                   h->stream, rm, h->eps_blk, h->r_sum, kuse, sl * kuse);
+        }
         return;
     }
     if (rm.nb == BB)
