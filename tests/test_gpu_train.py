@@ -44,13 +44,15 @@ def test_epoch_matches_oracle(lib, m, n, in_dim, classes, momentum):
     torch.cuda.synchronize()
     ref = oracle.train_epoch_softmax(X, y, perm, W0, None, lr, momentum)
     rows = out["grads"].cpu().numpy()
-    # fp32 model arithmetic against the double oracle: per-step rounding ~1e-7 relative,
-    # n steps of a contractive update -> well inside 1e-5 / 1e-4 at these sizes
+    # fp32 model arithmetic against the double oracle: per-step rounding ~1e-7 relative, a handful
+    # of steps of a contractive update: weights, velocity and every step's gradient rows are held
+    # to the 1e-5 relative L2 stated for per-example gradients
+    row_err = max(rel_l2(rows[:, j], ref["rows"][:, j]) for j in range(n))
+    v_err = rel_l2(v.cpu().numpy(), ref["v"]) if momentum else 0.0
+    print("W %.2e  v %.2e  rows %.2e" % (rel_l2(W.cpu().numpy(), ref["W"]), v_err, row_err))
     assert rel_l2(W.cpu().numpy(), ref["W"]) <= 1e-5
-    if momentum:
-        assert rel_l2(v.cpu().numpy(), ref["v"]) <= 1e-4
-    for j in range(n):
-        assert rel_l2(rows[:, j], ref["rows"][:, j]) <= 1e-4, j
+    assert v_err <= 1e-5
+    assert row_err <= 1e-5
     np.testing.assert_allclose(out["loss"].cpu().numpy(), ref["loss"], rtol=1e-4, atol=1e-6)
     # balancing: judged on the bytes the GPU balanced
     got = {"signs": out["signs"].cpu().numpy(), "perm": out["perm"].cpu().numpy()}
