@@ -296,12 +296,15 @@ def measure_config(name, args, steps, warmup, cpu_seconds):
         synth.set_input_drain(True, str(dev))
         res["inputs_flushed_to_hbm"] = extra_epochs(args.flush_steps)
         synth.set_input_drain(False, str(dev))
-        # the generator writing with each fixed store flavour
-        for other in ("plain", "streaming"):
-            if other != args.generator_stores:
-                synth.set_store_mode(other)
-                res["generator_with_%s_stores" % other] = extra_epochs(args.flush_steps)
+        # the generator writing with the store flavour the timed steps did not use
+        used = args.generator_stores
+        if used == "auto":   # the generator streams blocks larger than 384 MB (workloads/synth_hip.hip)
+            used = "streaming" if 8.0 * bb * d > (384 << 20) else "plain"
+        other = "plain" if used == "streaming" else "streaming"
+        synth.set_store_mode(other)
+        res["generator_with_%s_stores" % other] = extra_epochs(args.flush_steps)
         synth.set_store_mode(args.generator_stores)
+        res["inputs"] += " (%s stores for this block size)" % used
 
     if cpu_seconds > 0:
         res["cpu_baseline"] = cpu_oracle_sample(w, name, rows_src, grads, out["signs"].cpu().numpy(), d, m, n,
