@@ -52,7 +52,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c4_resnet18",
                     help="headline workload: one of the five configurations, or c2_train / c2_herding / "
-                         "c2_independent (the 'next' rows)")
+                         "c2_independent / syn_herding (the 'next' rows)")
     ap.add_argument("--others", default=None,
                     help="comma-separated workloads for the `workloads` array (default: the other four "
                          "configurations and the next rows when the headline is c4_resnet18, else none)")
@@ -320,6 +320,42 @@ def measure_config(name, args, steps, warmup, cpu_seconds):
     return res
 
 
+def measure_synthetic_herding(args, steps, warmup):
+    """The parallel herding objective on the vectors of the paper's synthetic study (App. E):
+    10^6 unit vectors in 16 dimensions (64-byte rows), 100 workers, random orders."""
+    import numpy as np
+    import torch
+
+    import paper_2302_00845_amd as pkg
+    import workloads
+
+    N, d, m = 1_000_000, 16, 100
+    n = N // m
+    dev = torch.device("cuda", 0)
+    z = torch.from_numpy(workloads.herding_vectors(args.seed, N, d).reshape(m, n, d)).to(dev)
+    perm = torch.from_numpy(workloads.random_perms(args.seed, m, n)).to(dev)
+    h = pkg.Handle(device=0)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    times = []
+    for it in range(warmup + steps):
+        e0.record()
+        b = pkg.cdgrab_herding_bound(h, z, perm)
+        e1.record()
+        torch.cuda.synchronize()
+        if it >= warmup:
+            times.append(e0.elapsed_time(e1))
+    ms = float(np.mean(times))
+    gbs = 2.0 * N * d * 4 / (ms * 1e-3) / 1e9          # every row is read twice
+    res = {"workload": "syn_herding", "metric": "examples/sec through the parallel herding objective",
+           "m": m, "n": n, "d": d, "examples": N, "steps": steps, "warmup": warmup, "value": N / (ms * 1e-3),
+           "unit": "examples/s", "ms_per_step": ms, "dtype": "f64", "herding_bound": float(b.cpu()[0]),
+           "roofline": {"kernel": "herding_segment_sums + herding_prefix_max", "bound": "hbm", "achieved": gbs,
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None},
+           "note": "128 MB of traffic in all: bound by the three dependent launches, not by bytes"}
+    h.close()
+    return res
+
+
 def measure_next_row(name, args, steps, warmup):
     """The rows built after the hot path, on config 2's problem: one training epoch of the softmax
     model (`c2_train`), one evaluation of the parallel herding objective on its gradients
@@ -329,6 +365,9 @@ def measure_next_row(name, args, steps, warmup):
 
     import paper_2302_00845_amd as pkg
     import workloads
+
+    if name == "syn_herding":
+        return measure_synthetic_herding(args, steps, warmup)
 
     w = workloads.CONFIGS["c2_softmax"]
     m, n, d = w.m, (args.n or w.n), w.d
@@ -402,7 +441,7 @@ def measure_next_row(name, args, steps, warmup):
     return res
 
 
-NEXT_ROWS = ("c2_train", "c2_herding", "c2_independent")
+NEXT_ROWS = ("c2_train", "c2_herding", "c2_independent", "syn_herding")
 
 
 def main():
