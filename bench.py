@@ -133,9 +133,8 @@ def cpu_oracle_sample(w, name, rows_src, grads, gpu_signs, d, m, n, bb, seconds,
         flips += int(differs.sum())
         agree = agree and not bool((differs & (np.abs(tt) > 1e-9 * nr * nc)).any())
     return {"value": 2 * sample_pairs / cpu_s, "unit": "examples/s", "cores": 1, "kind": "oracle",
-            "sample": "first %d flattened pairs (%d examples) of %s, rows copied from HBM in chunks of %d "
-                      "pairs; balancing loop only, the HIP path's signs imposed" % (
-                          sample_pairs, 2 * sample_pairs, name, chunk),
+            "sample": "first %d pairs (%d examples) of %s, rows copied from HBM; balancing loop only, "
+                      "the HIP path's signs imposed" % (sample_pairs, 2 * sample_pairs, name),
             "seconds": cpu_s, "host_cores_available": os.cpu_count(),
             "signs_agree_with_gpu_on_sample": agree, "in_margin_flips_on_sample": flips}
 
@@ -219,7 +218,7 @@ def measure_config(name, args, steps, warmup, cpu_seconds):
         "workload": name, "m": m, "n": n, "d": d, "examples": N, "steps": steps, "warmup": warmup,
         "value": N / (path_ms * 1e-3), "unit": "examples/s", "ms_per_step": path_ms,
         "block_pairs": bb, "blocks": blocks, "input": w.kind, "fused_apply": fused, "gram_ahead": ahead,
-        "inputs": ("written by the generator (store mode: %s) right before each block is balanced, not flushed"
+        "inputs": ("handed over by the generator right before each block, not flushed; store mode %s"
                    % args.generator_stores if w.kind == "stream" and not args.flush_inputs
                    else "resident in HBM"),
         "generator_ms_per_step": gen_ms, "wall_ms_per_step": wall_ms,
@@ -304,7 +303,7 @@ def measure_config(name, args, steps, warmup, cpu_seconds):
         synth.set_store_mode(other)
         res["generator_with_%s_stores" % other] = extra_epochs(args.flush_steps)
         synth.set_store_mode(args.generator_stores)
-        res["inputs"] += " (%s stores for this block size)" % used
+        res["inputs"] += " (%s stores)" % used
 
     if cpu_seconds > 0:
         res["cpu_baseline"] = cpu_oracle_sample(w, name, rows_src, grads, out["signs"].cpu().numpy(), d, m, n,
@@ -498,7 +497,60 @@ def main():
     line["kernels"] = head.get("kernels")
     line["cpu_baseline"] = head.get("cpu_baseline")
     line["workloads"] = array
-    print(json.dumps(line))
+    # Everything measured goes to stderr as one JSON document; stdout gets the ONE line of the
+    # contract, kept short (a few KB): the headline in full, the other workloads as compact entries.
+    print("bench detail: " + json.dumps(line), file=sys.stderr)
+    print(json.dumps(compact_line(line)))
+
+
+def _sig(x, digits=6):
+    """Floats rounded to `digits` significant digits, recursively (shorter JSON)."""
+    if isinstance(x, float):
+        return float("%.*g" % (digits, x))
+    if isinstance(x, dict):
+        return {k: _sig(v, digits) for k, v in x.items()}
+    if isinstance(x, (list, tuple)):
+        return [_sig(v, digits) for v in x]
+    return x
+
+
+def compact_line(line):
+    out = dict(line)
+    if out.get("roofline"):
+        out["roofline"] = {k: v for k, v in out["roofline"].items() if k != "traffic_source"}
+        out["roofline"]["traffic_note"] = "from profiles/ (rocprofv3 --pmc), not measured in this run"
+    for k in ("bytes_per_example", "balancer_achieved_GBs"):
+        out.pop(k, None)
+    for k in ("inputs_flushed_to_hbm", "generator_with_plain_stores", "generator_with_streaming_stores"):
+        if out.get(k):
+            out[k] = {a: b for a, b in out[k].items() if a in ("value", "ms_per_step", "balancer_hbm_frac",
+                                                               "kernels_avg_launch_ms")}
+    if out.get("kernels"):
+        out["kernels"] = {k: {"avg_launch_ms": v["avg_launch_ms"]} for k, v in out["kernels"].items()}
+    if out.get("cpu_baseline"):
+        out["cpu_baseline"] = {k: v for k, v in out["cpu_baseline"].items() if k != "host_cores_available"}
+    small = []
+    for w in out.get("workloads") or []:
+        e = {"workload": w["workload"], "m": w["m"], "n": w["n"], "d": w["d"], "value": w["value"],
+             "ms_per_step": w["ms_per_step"]}
+        if "balancer_hbm_frac" in w:
+            e["balancer_hbm_frac"] = w["balancer_hbm_frac"]
+        if w.get("inputs_flushed_to_hbm"):
+            e["flushed_hbm_frac"] = w["inputs_flushed_to_hbm"]["balancer_hbm_frac"]
+        if w.get("roofline"):
+            e["kernel"] = w["roofline"]["kernel"]
+            e["frac"] = w["roofline"]["frac"]
+            if "avg_launch_ms" in w["roofline"]:
+                e["avg_launch_ms"] = w["roofline"]["avg_launch_ms"]
+        if w.get("cpu_baseline"):
+            c = w["cpu_baseline"]
+            e["cpu_baseline"] = {"value": c["value"], "cores": c["cores"], "seconds": c["seconds"],
+                                 "signs_agree": c["signs_agree_with_gpu_on_sample"]}
+        if "note" in w and "launch" in w["note"]:
+            e["bound"] = "launch chain"
+        small.append(e)
+    out["workloads"] = small
+    return _sig(out)
 
 
 if __name__ == "__main__":
