@@ -116,10 +116,11 @@ int pick_block_pairs(int64_t pairs, int64_t d, int32_t requested) {
 }
 
 // Measured on MI355X: applying a block inside the next block's dot/Gram launch wins up
-// to about 3M elements per row (one launch and one read of the running sum less: 7 % at
-// 1M, 15 % at 8K); beyond that the heavier fused kernel streams 4-10 % slower than the
-// two lean ones.
-bool fuse_apply_by_default(int64_t d) { return d <= ((int64_t)1 << 21); }
+// to about 1.2M elements per row (one launch and one read of the running sum less: 3 % at
+// 1M, 4 % at 512K, 15 % at 8K); beyond that the heavier fused kernel streams 8-12 % slower
+// than the dot/Gram launch and the resident apply launch together (1.5M: 158 against 141 us
+// per 32-pair block, 2M: 213 against 198, 4M: 423 against 388).
+bool fuse_apply_by_default(int64_t d) { return d <= (int64_t)5 << 18; }
 
 // Dense input with short rows: a block is bound by its chain of launches, so the Gram
 // matrices (which depend on the rows only) are taken off the chain: one launch computes
@@ -262,8 +263,10 @@ void launch_pass1(cdgrab_handle *h, const RowMap &rm, const PrevBlock *prev, con
     }
 }
 // Rows from this length on take the resident form of the apply pass (the running-sum
-// traffic in one burst); shorter ones the flat form, whose launch ramps up faster.
-constexpr int64_t kResidentMinD = (int64_t)1 << 21;
+// traffic in one burst); shorter ones the flat form, whose launch ramps up faster
+// (block of 32 pairs, dot/Gram launch included: 1M elements 106 against 115 us, 768K 84
+// against 80 us).
+constexpr int64_t kResidentMinD = (int64_t)1 << 20;
 
 template <int BB, int VW>
 void launch_pass2(cdgrab_handle *h, const RowMap &rm, int groups) {
