@@ -288,6 +288,11 @@ def measure_config(name, args, steps, warmup, cpu_seconds):
             hq.close()
             r["kernels_avg_launch_ms"] = {"pass1_dots_gram": tq["pass1_ms"] / blocks,
                                           "pass2_apply": tq["pass2_ms"] / blocks}
+            if not fused and not ahead and tq["pass1_ms"] > 0 and tq["pass2_ms"] > 0:
+                pairs_blk = (N // 2) / blocks
+                r["kernels_hbm_frac"] = {
+                    "pass1_dots_gram": (8.0 * pairs_blk * d + 8.0 * d) / (tq["pass1_ms"] / blocks * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "pass2_apply": (8.0 * pairs_blk * d + 16.0 * d) / (tq["pass2_ms"] / blocks * 1e-3) / 1e9 / HBM_PEAK_GBS}
         return r
 
     if w.kind == "stream" and not args.flush_inputs and args.flush_steps > 0:
@@ -524,7 +529,7 @@ def compact_line(line):
     for k in ("inputs_flushed_to_hbm", "generator_with_plain_stores", "generator_with_streaming_stores"):
         if out.get(k):
             out[k] = {a: b for a, b in out[k].items() if a in ("value", "ms_per_step", "balancer_hbm_frac",
-                                                               "kernels_avg_launch_ms")}
+                                                               "kernels_avg_launch_ms", "kernels_hbm_frac")}
     if out.get("kernels"):
         out["kernels"] = {k: {"avg_launch_ms": v["avg_launch_ms"]} for k, v in out["kernels"].items()}
     if out.get("cpu_baseline"):
